@@ -1,0 +1,191 @@
+#!/usr/bin/env python3
+"""Benchmark of the segmented-gossip aggregation round on one MI355X.
+
+A step is one pass of the whole hot path over the resident arena: the round's peer
+table (hash kernel), the gather-average round (Eq. 3 / Eq. 4 of the segmented-gossip
+paper; for the fused workload the local SGD step first), and the swap of the front and
+back buffers.  The inputs are seeded and synthetic and already in HBM when the timed
+region starts.  Prints ONE JSON line: rounds per second, the roofline of the dominant
+kernel (the gather-average kernel, HBM bound) measured with HIP events on the launch
+stream, and the CPU oracle timed on the host as a reported baseline.
+
+usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+"""
+import argparse
+import hashlib
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
+
+
+def kernel_source_digest():
+    h = hashlib.sha256()
+    for f in ("gossip_round.hip", "combo_internal.h"):
+        h.update(open(os.path.join(ROOT, "paper_1908_07782_amd", "csrc", f), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def recorded_traffic(workload):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc
+    summary, or None when there is none or the kernel source changed since."""
+    path = os.path.join(ROOT, "profiles", f"gossip_round_kernel_{workload}_pmc.txt")
+    if not os.path.exists(path):
+        return None
+    text = open(path).read()
+    m = re.search(r"^kernel_source_digest:\s*(\w+)", text, flags=re.M)
+    t = re.search(r"^hbm_bytes_per_launch:\s*([0-9.eE+]+)", text, flags=re.M)
+    if not m or not t or m.group(1) != kernel_source_digest():
+        return None
+    return float(t.group(1))
+
+
+def cpu_baseline(wl, X0_host, budget_s=20.0):
+    """The oracle as it stands (single thread), timed on whole rounds of the same
+    workload until about `budget_s` seconds of CPU work are spent."""
+    import numpy as np
+    from oracle import ref
+    X = X0_host
+    Y = np.empty_like(X)
+    G = None
+    if wl.fused:
+        G = (np.random.default_rng(1).standard_normal(X.shape, dtype=np.float32) * wl.grad_std)
+    t0 = time.perf_counter()
+    rounds = 0
+    while True:
+        ph = ref.make_peer_table(wl.N, wl.S, wl.R, wl.hash_seed, rounds)
+        if wl.fused:
+            Y = ref.local_sgd_then_gossip(X, G, wl.lr, ph, wl.P, wl.S, wl.R)
+        else:
+            ref.gossip_round(X, ph, wl.P, wl.S, wl.R, out=Y)
+        X, Y = Y, X
+        rounds += 1
+        dt = time.perf_counter() - t0
+        if dt >= budget_s or rounds >= wl.rounds:
+            break
+    return {"value": rounds / dt, "unit": "rounds/s", "cores": 1, "kind": "oracle",
+            "sample": f"{rounds} full rounds of {wl.name} (all N={wl.N} workers, all P={wl.P} "
+                      f"columns), single thread, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c2_resnet18")
+    ap.add_argument("--tile", type=int, default=0, help="override COMBO_TUNE_TILE_COLS")
+    ap.add_argument("--swizzle", type=int, default=-1, help="override COMBO_TUNE_XCD_SWIZZLE")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (all N simulated workers live in one "
+                 "arena); --gpus must be 1")
+
+    import torch
+    import paper_1908_07782_amd as combo
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    combo.lib()
+    if args.tile:
+        combo.tune(combo.TUNE_TILE_COLS, args.tile)
+    if args.swizzle >= 0:
+        combo.tune(combo.TUNE_XCD_SWIZZLE, args.swizzle)
+    wl = combo.workloads.WORKLOADS[args.workload]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    arena = torch.zeros((2, wl.N, wl.ld), dtype=torch.float32, device=dev)
+    combo.workloads.fill_params(arena[0], wl)
+    grads = None
+    if wl.fused:
+        grads = torch.zeros((wl.N, wl.ld), dtype=torch.float32, device=dev)
+        combo.workloads.fill_grads(grads, wl, 0)
+    peers = torch.empty(max(wl.N * wl.S * wl.R, 1), dtype=torch.int32, device=dev)
+    X0_host = None
+    if not args.no_cpu_baseline:
+        X0_host = arena[0, :, :wl.P].cpu().numpy()
+    stream = torch.cuda.current_stream()
+
+    state = {"cur": 0, "round": 0}
+
+    def step(ev=None):
+        cur, rnd = state["cur"], state["round"]
+        combo.make_peer_table(peers, wl.N, wl.S, wl.R, wl.hash_seed, rnd, stream=stream)
+        if ev is not None:
+            ev[0].record(stream)
+        if wl.fused:
+            combo.local_sgd_then_gossip(arena[1 - cur], arena[cur], grads, wl.lr, peers, wl.P, wl.S,
+                                        wl.R, stream=stream)
+        else:
+            combo.segment_gossip_round(arena[1 - cur], arena[cur], peers, wl.P, wl.S, wl.R,
+                                       stream=stream)
+        if ev is not None:
+            ev[1].record(stream)
+        state["cur"], state["round"] = 1 - cur, rnd + 1
+
+    for _ in range(args.warmup):
+        step()
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(events[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    wall = t1 - t0
+    kern_ms = sorted(a.elapsed_time(b) for a, b in events)
+    kern_avg_ms = sum(kern_ms) / len(kern_ms)
+    alg_bytes = wl.algorithmic_bytes_per_round
+    if wl.fused:
+        alg_bytes += 4 * 3 * wl.N * wl.P          # in-place step: read x, read g, write x
+    achieved = alg_bytes / (kern_avg_ms * 1e-3) / 1e9
+    out = {
+        "metric": "gossip rounds/sec and effective HBM GB/s (% of peak) at N workers x P params",
+        "value": args.steps / wall,
+        "unit": "rounds/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall / args.steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "N": wl.N, "P": wl.P, "S": wl.S, "R": wl.R,
+                   "fused_local_step": wl.fused, "tile_cols": combo.get_tune(combo.TUNE_TILE_COLS),
+                   "xcd_swizzle": combo.get_tune(combo.TUNE_XCD_SWIZZLE)},
+        "effective_hbm_gbs": alg_bytes / (wall / args.steps) / 1e9,
+        "effective_hbm_pct_of_peak": 100.0 * alg_bytes / (wall / args.steps) / 1e9 / HBM_PEAK_GBS,
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "gossip_round_kernel" + (" (+ sgd_step_kernel)" if wl.fused else ""),
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": recorded_traffic(wl.name),
+            "algorithmic_bytes_per_launch": alg_bytes,
+            "compulsory_bytes_per_launch": 8 * wl.N * wl.P + (4 * wl.N * wl.P if wl.fused else 0),
+            "kernel_ms_avg": kern_avg_ms,
+            "kernel_ms_median": kern_ms[len(kern_ms) // 2],
+            "kernel_ms_min": kern_ms[0],
+        },
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, X0_host)
+        out["cpu_baseline"]["host_cores_visible"] = os.cpu_count()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,142 @@
+/*
+ * combo.h - C ABI of the segmented-gossip aggregation round on one AMD MI355X (gfx950).
+ *
+ * The method is the model aggregation of "Decentralized Federated Learning: A Segmented
+ * Gossip Approach" (Hu, Jiang, Wang; arXiv 1908.07782):  N simulated workers each hold a
+ * flat parameter vector of P values, cut into S contiguous, non-overlapping segments
+ * (Sec. 3, Eq. 1).  In every round each worker chooses, for each segment, R other
+ * workers (Sec. 4.1 step 2) and replaces the segment by the weighted mean of its own
+ * copy and the R pulled copies (Sec. 3, Eq. 3); the aggregated segments together are the
+ * new model (Eq. 4).  All pulled segments are the providers' state from before the
+ * aggregation of the same round (Sec. 4.1 steps 3-4, Sec. 5.1: synchronous process).
+ *
+ * Conventions common to every entry point
+ *   - Pointers named d_* are DEVICE pointers (HIP global memory of the current device).
+ *     The library never allocates, frees or copies device memory and never
+ *     synchronises: work is enqueued on `stream` (a hipStream_t passed as void*;
+ *     NULL = the default stream) and the call returns at once.  The caller owns every
+ *     buffer and must keep it alive until the stream has passed the enqueued work.
+ *   - Return value: COMBO_OK (0) or a negative combo_status.  On an error nothing has
+ *     been enqueued.  No exceptions, no aborts.
+ *   - Parameter matrices are row-major float32 [N][ld]: worker w's parameter e is at
+ *     index w*ld + e, e in [0, P).  ld >= P is the row pitch in elements.  The padding
+ *     columns [P, ld) are never read and never written.
+ *   - Segment s in [0, S) covers columns [s*L, (s+1)*L) with L = floor(P/S), except the
+ *     last, which extends to P (it absorbs the remainder).  Requires 1 <= S <= P.
+ *   - A peer table is int32 [N][S][R], worker-major: entry (w*S + s)*R + j is the j-th
+ *     provider of segment s for worker w.  The order of the j axis is the order of
+ *     summation.  Entries must lie in [0, N); the aggregation entry points do not
+ *     check the contents of a table (they are device data) - out-of-range entries are
+ *     undefined behaviour.
+ *   - Arithmetic is IEEE binary32 with one rounding per operation (no fused
+ *     multiply-add), in the fixed order stated at each entry point, so results are
+ *     reproducible bit for bit.
+ *   - Fast paths need 16-byte aligned d_dst/d_src/d_grad and ld % 4 == 0; any other
+ *     alignment or pitch is accepted and handled by a slower scalar kernel.
+ *   - Thread safety: calls are independent; tuning (combo_tune) is process-global.
+ */
+#ifndef COMBO_H_
+#define COMBO_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    COMBO_OK = 0,
+    COMBO_EINVAL = -1, /* a size or pointer argument is invalid (see each function)      */
+    COMBO_EALIAS = -2, /* output overlaps an input that must stay intact during the round */
+    COMBO_ERANGE = -3, /* valid in principle but beyond what this build supports          */
+    COMBO_EHIP = -4    /* the HIP runtime reported an error when enqueuing                */
+} combo_status;
+
+/*
+ * Peer selection for one round (Sec. 4.1 step 2: R targets per segment, drawn at random
+ * among the other workers without replacement).
+ *
+ * For every (w, s) the R entries are the first R elements of a Fisher-Yates shuffle of
+ * the N-1 other workers (listed in increasing order, w skipped).  Step j in [0, R)
+ * swaps position j with position j + reduce(hash(seed, round, w, s, j), N-1-j), where
+ *   mix64(z):  z = (z ^ z>>30) * 0xBF58476D1CE4E5B9; z = (z ^ z>>27) * 0x94D049BB133111EB;
+ *              return z ^ z>>31                                  (SplitMix64 finaliser)
+ *   hash:      h = mix64(seed + G); then for c in (round, w, s, j): h = mix64((h ^ c) + G)
+ *              with G = 0x9E3779B97F4A7C15
+ *   reduce(h, m) = ((h >> 32) * m) >> 32.
+ * The table is a pure function of (N, S, R, seed, round): any entry can be recomputed
+ * anywhere, nothing is carried from round to round.
+ *
+ *   d_peers  out, device, int32[N*S*R]; may be NULL when R == 0 (nothing is written).
+ * Errors: COMBO_EINVAL for N < 1, S < 1, R < 0, R > N-1 (R distinct others do not
+ * exist), or d_peers == NULL with R > 0.  COMBO_ERANGE for N > 16384 (the shuffle
+ * state of one (w, s) is kept in 64 KiB of LDS).
+ */
+int combo_make_peer_table(int32_t* d_peers, int32_t N, int32_t S, int32_t R,
+                          uint64_t seed, uint64_t round, void* stream);
+
+/*
+ * One aggregation round: Eq. (3) on every segment of every worker, written to the back
+ * buffer (Eq. 4), all reads from the front buffer.
+ *
+ *   uniform weights (d_dataset_sizes == NULL):
+ *       acc = src[w][e]; acc += src[p_0][e]; ...; acc += src[p_{R-1}][e];
+ *       dst[w][e] = acc * (1.0f / (float)(R + 1))
+ *   dataset-size weights (d_dataset_sizes = |D_j|, device float32[N], all > 0):
+ *       num = d[w]*src[w][e]; num += d[p_j]*src[p_j][e] for j = 0..R-1 (product rounded,
+ *       then the sum); den = d[w] + d[p_0] + ... + d[p_{R-1}] in that order;
+ *       dst[w][e] = num / den
+ *   with p_j = d_peers[(w*S + seg(e))*R + j].
+ *
+ *   d_dst    out, device, float32[N][ld]; every element [w][0..P) is written exactly once.
+ *   d_src    in,  device, float32[N][ld]; not modified.
+ *   d_peers  in,  device, int32[N*S*R]; may be NULL when R == 0 (the round is a copy).
+ * Errors: COMBO_EINVAL for N < 1, S < 1, S > P, R < 0, R > N-1, ld < P, a NULL d_dst or
+ * d_src, NULL d_peers with R > 0; COMBO_EALIAS if [d_dst, d_dst + N*ld) overlaps
+ * [d_src, d_src + N*ld) (a worker would read a neighbour's already aggregated values);
+ * COMBO_ERANGE if N*ceil(P/tile) exceeds the grid limit of 2^31-1 workgroups.
+ */
+int combo_segment_gossip_round(float* d_dst, const float* d_src, int64_t ld,
+                               const int32_t* d_peers, const float* d_dataset_sizes,
+                               int32_t N, int64_t P, int32_t S, int32_t R, void* stream);
+
+/*
+ * Local update, then the round (Sec. 4.1 steps 1, 3, 4): first EVERY worker takes one
+ * SGD step with the given gradient, x' = x - lr*g (product rounded, then the
+ * difference), and only then Eq. (3) is applied to the stepped parameters x' exactly as
+ * in combo_segment_gossip_round.
+ *
+ *   d_src   in/out, device, float32[N][ld]: on return it holds the stepped parameters x'
+ *           (the step is applied in place, which is also what makes every reader see
+ *           post-update values).
+ *   d_grad  in, device, float32[N][ld], same pitch; not modified.
+ * Errors: as combo_segment_gossip_round, plus COMBO_EINVAL for a NULL d_grad and
+ * COMBO_EALIAS if d_grad overlaps d_src or d_dst.
+ */
+int combo_local_sgd_then_gossip(float* d_dst, float* d_src, const float* d_grad, float lr,
+                                int64_t ld, const int32_t* d_peers,
+                                const float* d_dataset_sizes, int32_t N, int64_t P, int32_t S,
+                                int32_t R, void* stream);
+
+/*
+ * Performance knobs (process-global, host side only; results never depend on them).
+ *   COMBO_TUNE_TILE_COLS   columns of one worker handled by one workgroup:
+ *                          1024, 2048 or 4096 (256 threads x 1, 2 or 4 float4 each)
+ *   COMBO_TUNE_XCD_SWIZZLE 1: consecutive workgroups on one XCD are the N workers of
+ *                          one column tile (peer rows are re-read from that XCD's L2);
+ *                          0: plain worker-major order
+ *   COMBO_TUNE_FUSED_MODE  0: in-place step kernel then the round (what
+ *                          combo_local_sgd_then_gossip documents); no other mode yet
+ * Returns COMBO_OK or COMBO_EINVAL for an unknown key or unsupported value.
+ */
+enum { COMBO_TUNE_TILE_COLS = 0, COMBO_TUNE_XCD_SWIZZLE = 1, COMBO_TUNE_FUSED_MODE = 2 };
+int combo_tune(int key, int value);
+int combo_get_tune(int key); /* current value, or COMBO_EINVAL */
+
+/* Static, human-readable text for a status code. Never NULL. */
+const char* combo_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COMBO_H_ */

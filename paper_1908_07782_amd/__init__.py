@@ -1,0 +1,11 @@
+"""Segmented-gossip aggregation round on one MI355X: thin Python binding of libcombo.
+
+The functions below have the names and argument order of the C ABI (include/combo.h)
+and only marshal arguments: torch tensors supply device memory and the stream, every
+step of the round runs in the library's HIP kernels.  There is no CPU fallback: if the
+shared library has not been built, importing the binding's functions raises.
+"""
+from . import workloads  # noqa: F401
+from .binding import (ComboError, get_tune, lib, local_sgd_then_gossip, make_peer_table,  # noqa: F401
+                      segment_gossip_round, strerror, tune, TUNE_FUSED_MODE, TUNE_TILE_COLS,
+                      TUNE_XCD_SWIZZLE, LIB_PATH)

@@ -1,0 +1,131 @@
+"""ctypes binding of libcombo.so - argument marshalling only."""
+import ctypes
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libcombo.so")
+
+TUNE_TILE_COLS = 0
+TUNE_XCD_SWIZZLE = 1
+TUNE_FUSED_MODE = 2
+
+EXPORTS = ("combo_make_peer_table", "combo_segment_gossip_round", "combo_local_sgd_then_gossip",
+           "combo_tune", "combo_get_tune", "combo_strerror")
+
+_LIB = None
+
+
+class ComboError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} (status {status})")
+
+
+def lib():
+    """Load libcombo.so (built by paper_1908_07782_amd/build.py).  Fails loudly."""
+    global _LIB
+    if _LIB is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_1908_07782_amd.build` "
+                              "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, u64, f32 = (ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64,
+                                  ctypes.c_float)
+        L.combo_make_peer_table.argtypes = [vp, i32, i32, i32, u64, u64, vp]
+        L.combo_make_peer_table.restype = ctypes.c_int
+        L.combo_segment_gossip_round.argtypes = [vp, vp, i64, vp, vp, i32, i64, i32, i32, vp]
+        L.combo_segment_gossip_round.restype = ctypes.c_int
+        L.combo_local_sgd_then_gossip.argtypes = [vp, vp, vp, f32, i64, vp, vp, i32, i64, i32, i32, vp]
+        L.combo_local_sgd_then_gossip.restype = ctypes.c_int
+        L.combo_tune.argtypes = [ctypes.c_int, ctypes.c_int]
+        L.combo_tune.restype = ctypes.c_int
+        L.combo_get_tune.argtypes = [ctypes.c_int]
+        L.combo_get_tune.restype = ctypes.c_int
+        L.combo_strerror.argtypes = [ctypes.c_int]
+        L.combo_strerror.restype = ctypes.c_char_p
+        _LIB = L
+    return _LIB
+
+
+def strerror(status):
+    return lib().combo_strerror(int(status)).decode()
+
+
+def tune(key, value):
+    rc = lib().combo_tune(int(key), int(value))
+    if rc:
+        raise ComboError(rc, "combo_tune")
+
+
+def get_tune(key):
+    return lib().combo_get_tune(int(key))
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _dev_ptr(t, dtype, name, optional=False):
+    if t is None:
+        if optional:
+            return None
+        raise ValueError(f"{name} is required")
+    if not (t.is_cuda and t.dtype == dtype):
+        raise ValueError(f"{name}: need a {dtype} tensor in device memory")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _matrix(t, name):
+    if not (t.dim() == 2 and t.stride(1) == 1):
+        raise ValueError(f"{name}: need a 2-D tensor whose rows are contiguous (row pitch allowed)")
+    return t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1])
+
+
+def make_peer_table(peers, N, S, R, seed, rnd, stream=None):
+    """combo_make_peer_table: fills the int32 device tensor `peers` (N*S*R entries)."""
+    if R > 0 and (peers is None or peers.numel() < N * S * R or not peers.is_contiguous()):
+        raise ValueError("peers: need a contiguous int32 device tensor with N*S*R entries")
+    rc = lib().combo_make_peer_table(_dev_ptr(peers, torch.int32, "peers", optional=(R == 0)),
+                                     N, S, R, ctypes.c_uint64(seed), ctypes.c_uint64(rnd),
+                                     _stream_ptr(stream))
+    if rc:
+        raise ComboError(rc, "combo_make_peer_table")
+    return peers
+
+
+def segment_gossip_round(dst, src, peers, P, S, R, dataset_sizes=None, stream=None):
+    """combo_segment_gossip_round on (N, ld)-strided float32 device tensors dst, src."""
+    N = src.shape[0]
+    ld = _matrix(src, "src")
+    if _matrix(dst, "dst") != ld or dst.shape[0] != N:
+        raise ValueError("dst must have src's row count and pitch")
+    rc = lib().combo_segment_gossip_round(
+        _dev_ptr(dst, torch.float32, "dst"), _dev_ptr(src, torch.float32, "src"), ld,
+        _dev_ptr(peers, torch.int32, "peers", optional=(R == 0)),
+        _dev_ptr(dataset_sizes, torch.float32, "dataset_sizes", optional=True),
+        N, P, S, R, _stream_ptr(stream))
+    if rc:
+        raise ComboError(rc, "combo_segment_gossip_round")
+    return dst
+
+
+def local_sgd_then_gossip(dst, src, grad, lr, peers, P, S, R, dataset_sizes=None, stream=None):
+    """combo_local_sgd_then_gossip: src is stepped in place, dst receives the round."""
+    N = src.shape[0]
+    ld = _matrix(src, "src")
+    if _matrix(dst, "dst") != ld or _matrix(grad, "grad") != ld or dst.shape[0] != N \
+            or grad.shape[0] != N:
+        raise ValueError("dst and grad must have src's row count and pitch")
+    rc = lib().combo_local_sgd_then_gossip(
+        _dev_ptr(dst, torch.float32, "dst"), _dev_ptr(src, torch.float32, "src"),
+        _dev_ptr(grad, torch.float32, "grad"), ctypes.c_float(lr), ld,
+        _dev_ptr(peers, torch.int32, "peers", optional=(R == 0)),
+        _dev_ptr(dataset_sizes, torch.float32, "dataset_sizes", optional=True),
+        N, P, S, R, _stream_ptr(stream))
+    if rc:
+        raise ComboError(rc, "combo_local_sgd_then_gossip")
+    return dst

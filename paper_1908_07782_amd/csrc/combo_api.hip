@@ -1,0 +1,139 @@
+// The C ABI of libcombo: argument validation and kernel launches.  See include/combo.h
+// for the meaning of every argument; nothing here allocates, copies or synchronises.
+#include "../../include/combo.h"
+
+#include <atomic>
+
+#include "combo_internal.h"
+
+namespace {
+
+std::atomic<int> g_tile_cols{2048};
+std::atomic<int> g_swizzle{1};
+std::atomic<int> g_fused_mode{0};
+
+bool overlaps(const void* a, uint64_t a_bytes, const void* b, uint64_t b_bytes) {
+    const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+    return a0 < b0 + b_bytes && b0 < a0 + a_bytes;
+}
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+// shared checks of the two aggregation entry points
+int check_round_args(const float* dst, const float* src, int64_t ld, const int32_t* peers,
+                     int32_t N, int64_t P, int32_t S, int32_t R) {
+    if (N < 1 || S < 1 || P < 1 || (int64_t)S > P || R < 0 || R > N - 1) return COMBO_EINVAL;
+    if (ld < P || dst == nullptr || src == nullptr) return COMBO_EINVAL;
+    if (R > 0 && peers == nullptr) return COMBO_EINVAL;
+    const uint64_t bytes = (uint64_t)N * (uint64_t)ld * sizeof(float);
+    if (overlaps(dst, bytes, src, bytes)) return COMBO_EALIAS;
+    return COMBO_OK;
+}
+
+int enqueue_round(float* dst, const float* src, int64_t ld, const int32_t* peers,
+                  const float* dsz, int32_t N, int64_t P, int32_t S, int32_t R, hipStream_t st) {
+    const int tile_cols = g_tile_cols.load();
+    const bool swizzle = g_swizzle.load() != 0;
+    if (combo::round_grid_size(N, P, tile_cols, swizzle) == 0) return COMBO_ERANGE;
+    combo::RoundArgs a;
+    a.dst = dst;
+    a.src = src;
+    a.peers = peers;
+    a.dsz = dsz;
+    a.ld = ld;
+    a.P = P;
+    a.L = P / S;
+    a.N = N;
+    a.S = S;
+    a.R = R;
+    a.tiles_per_row = (uint32_t)(((uint64_t)P + (uint64_t)tile_cols - 1) / (uint64_t)tile_cols);
+    a.swizzle = swizzle ? 1 : 0;
+    a.p32 = P < (int64_t)0x100000000ll ? 1 : 0;
+    a.inv = 1.0f / (float)(R + 1);
+    const bool vec = aligned16(dst) && aligned16(src) && (ld % 4 == 0);
+    return combo::launch_round(a, tile_cols, vec, st) == hipSuccess ? COMBO_OK : COMBO_EHIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int combo_make_peer_table(int32_t* d_peers, int32_t N, int32_t S, int32_t R, uint64_t seed,
+                          uint64_t round, void* stream) {
+    if (N < 1 || S < 1 || R < 0 || R > N - 1) return COMBO_EINVAL;
+    if (R == 0) return COMBO_OK;                       // empty table
+    if (d_peers == nullptr) return COMBO_EINVAL;
+    if (N > 16384 || (uint64_t)N * (uint64_t)S > 0x7FFFFFFFull) return COMBO_ERANGE;
+    const hipError_t e = combo::launch_peer_table(d_peers, N, S, R, seed, round,
+                                                  (hipStream_t)stream);
+    return e == hipSuccess ? COMBO_OK : COMBO_EHIP;
+}
+
+int combo_segment_gossip_round(float* d_dst, const float* d_src, int64_t ld,
+                               const int32_t* d_peers, const float* d_dataset_sizes, int32_t N,
+                               int64_t P, int32_t S, int32_t R, void* stream) {
+    const int rc = check_round_args(d_dst, d_src, ld, d_peers, N, P, S, R);
+    if (rc != COMBO_OK) return rc;
+    return enqueue_round(d_dst, d_src, ld, d_peers, d_dataset_sizes, N, P, S, R,
+                         (hipStream_t)stream);
+}
+
+int combo_local_sgd_then_gossip(float* d_dst, float* d_src, const float* d_grad, float lr,
+                                int64_t ld, const int32_t* d_peers, const float* d_dataset_sizes,
+                                int32_t N, int64_t P, int32_t S, int32_t R, void* stream) {
+    const int rc = check_round_args(d_dst, d_src, ld, d_peers, N, P, S, R);
+    if (rc != COMBO_OK) return rc;
+    if (d_grad == nullptr) return COMBO_EINVAL;
+    const uint64_t bytes = (uint64_t)N * (uint64_t)ld * sizeof(float);
+    if (overlaps(d_grad, bytes, d_src, bytes) || overlaps(d_grad, bytes, d_dst, bytes))
+        return COMBO_EALIAS;
+    if (combo::round_grid_size(N, P, g_tile_cols.load(), g_swizzle.load() != 0) == 0 ||
+        combo::round_grid_size(N, P, 4096, false) == 0)
+        return COMBO_ERANGE;
+    const bool vec = aligned16(d_src) && aligned16(d_grad) && (ld % 4 == 0);
+    if (combo::launch_sgd_step(d_src, d_grad, lr, ld, N, P, vec, (hipStream_t)stream) != hipSuccess)
+        return COMBO_EHIP;
+    return enqueue_round(d_dst, d_src, ld, d_peers, d_dataset_sizes, N, P, S, R,
+                         (hipStream_t)stream);
+}
+
+int combo_tune(int key, int value) {
+    switch (key) {
+        case COMBO_TUNE_TILE_COLS:
+            if (value != 1024 && value != 2048 && value != 4096) return COMBO_EINVAL;
+            g_tile_cols.store(value);
+            return COMBO_OK;
+        case COMBO_TUNE_XCD_SWIZZLE:
+            if (value != 0 && value != 1) return COMBO_EINVAL;
+            g_swizzle.store(value);
+            return COMBO_OK;
+        case COMBO_TUNE_FUSED_MODE:
+            if (value != 0) return COMBO_EINVAL;
+            g_fused_mode.store(value);
+            return COMBO_OK;
+        default:
+            return COMBO_EINVAL;
+    }
+}
+
+int combo_get_tune(int key) {
+    switch (key) {
+        case COMBO_TUNE_TILE_COLS: return g_tile_cols.load();
+        case COMBO_TUNE_XCD_SWIZZLE: return g_swizzle.load();
+        case COMBO_TUNE_FUSED_MODE: return g_fused_mode.load();
+        default: return COMBO_EINVAL;
+    }
+}
+
+const char* combo_strerror(int status) {
+    switch (status) {
+        case COMBO_OK: return "success";
+        case COMBO_EINVAL: return "invalid argument (size out of range or required pointer is NULL)";
+        case COMBO_EALIAS: return "buffers overlap: the round needs disjoint front, back and gradient buffers";
+        case COMBO_ERANGE: return "argument beyond the supported range (grid or LDS limit)";
+        case COMBO_EHIP: return "the HIP runtime reported an error while enqueuing";
+        default: return "unknown combo status";
+    }
+}
+
+}  // extern "C"

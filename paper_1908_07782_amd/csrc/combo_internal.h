@@ -1,0 +1,41 @@
+// Internal declarations shared by the translation units of libcombo (HIP path only).
+#ifndef COMBO_INTERNAL_H_
+#define COMBO_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace combo {
+
+constexpr int kThreads = 256;          // 4 wavefronts of 64 lanes per workgroup
+constexpr int kXcds = 8;               // accelerator complex dies of one MI355X
+constexpr int kMaxTemplatedR = 8;      // replica counts with a fully unrolled kernel
+
+// Arguments of one aggregation round, passed by value to the kernels.
+struct RoundArgs {
+    float* dst;
+    const float* src;
+    const int32_t* peers;
+    const float* dsz;        // dataset sizes |D_j| or nullptr (uniform weights)
+    int64_t ld;              // row pitch in elements
+    int64_t P;               // parameters per worker
+    int64_t L;               // floor(P / S): length of every segment but the last
+    int32_t N, S, R;
+    uint32_t tiles_per_row;  // ceil(P / tile columns)
+    int32_t swizzle;         // 1: XCD-aware workgroup order
+    int32_t p32;             // 1: P < 2^32, segment lookup may divide in 32 bits
+    float inv;               // 1.0f / (float)(R + 1)
+};
+
+// launchers (defined in gossip_round.hip / peer_table.hip); return hipGetLastError()
+hipError_t launch_round(const RoundArgs& a, int tile_cols, bool vec, hipStream_t st);
+hipError_t launch_sgd_step(float* x, const float* g, float lr, int64_t ld, int32_t N, int64_t P,
+                           bool vec, hipStream_t st);
+hipError_t launch_peer_table(int32_t* peers, int32_t N, int32_t S, int32_t R, uint64_t seed,
+                             uint64_t round, hipStream_t st);
+
+// number of workgroups launch_round would use, or 0 if that exceeds the grid limit
+uint64_t round_grid_size(int32_t N, int64_t P, int tile_cols, bool swizzle);
+
+}  // namespace combo
+#endif

@@ -1,0 +1,114 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, and rejects bad arguments before touching the device.
+(The error paths return before any HIP call, so fake non-NULL pointers are safe.)"""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    import paper_1908_07782_amd as combo
+    if not os.path.exists(combo.LIB_PATH):
+        from paper_1908_07782_amd import build
+        build.build()
+    return combo.lib()
+
+
+def test_every_declared_symbol_is_exported(L):
+    header = open(os.path.join(ROOT, "include", "combo.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(combo_[a-z0-9_]+)\s*\(", header))
+    assert {"combo_make_peer_table", "combo_segment_gossip_round",
+            "combo_local_sgd_then_gossip", "combo_strerror"} <= declared
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_no_torch_or_oracle_in_the_boundary():
+    header = open(os.path.join(ROOT, "include", "combo.h")).read()
+    assert "torch" not in header.lower() and "at::" not in header
+    for dirpath, _, files in os.walk(os.path.join(ROOT, "paper_1908_07782_amd")):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(from|import)\s+\.*oracle", text, flags=re.M), f
+                assert "combo_ref" not in text and "oracle/" not in text, f
+
+
+def test_strerror_is_total(L):
+    for code in range(-6, 2):
+        s = L.combo_strerror(code)
+        assert s and len(s) > 3
+
+
+FAKE_A = ctypes.c_void_p(0x10000000)
+FAKE_B = ctypes.c_void_p(0x20000000)
+FAKE_C = ctypes.c_void_p(0x30000000)
+FAKE_T = ctypes.c_void_p(0x40000000)
+EINVAL, EALIAS, ERANGE = -1, -2, -3
+
+
+def test_peer_table_argument_errors(L):
+    f = L.combo_make_peer_table
+    assert f(FAKE_T, 0, 1, 0, 0, 0, None) == EINVAL          # N < 1
+    assert f(FAKE_T, 4, 0, 1, 0, 0, None) == EINVAL          # S < 1
+    assert f(FAKE_T, 4, 2, -1, 0, 0, None) == EINVAL         # R < 0
+    assert f(FAKE_T, 4, 2, 4, 0, 0, None) == EINVAL          # R > N-1
+    assert f(None, 4, 2, 1, 0, 0, None) == EINVAL            # NULL table with R > 0
+    assert f(None, 4, 2, 0, 0, 0, None) == 0                 # R == 0: empty table, nothing to do
+    assert f(FAKE_T, 16385, 2, 1, 0, 0, None) == ERANGE      # LDS limit
+
+
+def test_round_argument_errors(L):
+    f = L.combo_segment_gossip_round
+    ok = dict(N=4, P=1000, S=4, R=2, ld=1024)
+
+    def call(dst=FAKE_A, src=FAKE_B, peers=FAKE_T, d=None, **kw):
+        a = dict(ok, **kw)
+        return f(dst, src, a["ld"], peers, d, a["N"], a["P"], a["S"], a["R"], None)
+
+    assert call(N=0) == EINVAL
+    assert call(S=0) == EINVAL
+    assert call(S=1001) == EINVAL                 # more segments than parameters
+    assert call(R=-1) == EINVAL
+    assert call(R=4) == EINVAL                    # needs R <= N-1
+    assert call(ld=999) == EINVAL                 # pitch shorter than a row
+    assert call(dst=None) == EINVAL
+    assert call(src=None) == EINVAL
+    assert call(peers=None) == EINVAL
+    assert call(dst=FAKE_A, src=FAKE_A) == EALIAS
+    # back buffer starting inside the front buffer (4 rows x 1024 floats = 16 KiB)
+    assert call(dst=ctypes.c_void_p(0x20000000 + 4 * 1024 * 4 - 4), src=FAKE_B) == EALIAS
+    assert call(dst=ctypes.c_void_p(0x20000000 - 4 * 1024 * 4 + 4), src=FAKE_B) == EALIAS
+    # grid limit: N * ceil(P / tile) must stay below 2^31
+    assert f(FAKE_A, ctypes.c_void_p(0x7000000000000000), 1 << 40, FAKE_T, None, 16384, 1 << 40, 4, 2,
+             None) == ERANGE
+
+
+def test_fused_argument_errors(L):
+    f = L.combo_local_sgd_then_gossip
+
+    def call(dst=FAKE_A, src=FAKE_B, grad=FAKE_C, peers=FAKE_T, N=4, P=1000, S=4, R=2, ld=1024):
+        return f(dst, src, grad, ctypes.c_float(0.01), ld, peers, None, N, P, S, R, None)
+
+    assert call(grad=None) == EINVAL
+    assert call(grad=FAKE_B) == EALIAS
+    assert call(grad=FAKE_A) == EALIAS
+    assert call(dst=FAKE_B) == EALIAS
+    assert call(R=9) == EINVAL
+
+
+def test_tuning_knobs(L):
+    assert L.combo_tune(0, 1000) == EINVAL
+    assert L.combo_tune(99, 1) == EINVAL
+    old = L.combo_get_tune(0)
+    for v in (1024, 2048, 4096):
+        assert L.combo_tune(0, v) == 0 and L.combo_get_tune(0) == v
+    assert L.combo_tune(0, old) == 0
+    assert L.combo_get_tune(1) in (0, 1)
+    assert L.combo_get_tune(77) == EINVAL
