@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
 
 def kernel_source_digest():
     h = hashlib.sha256()
-    for f in ("gossip_round.hip", "combo_internal.h"):
+    for f in ("gossip_slab.hip", "gossip_round.hip", "round_device.h", "combo_internal.h"):
         h.update(open(os.path.join(ROOT, "paper_1908_07782_amd", "csrc", f), "rb").read())
     return h.hexdigest()[:16]
 
@@ -82,6 +82,12 @@ def main():
     ap.add_argument("--workload", default="c2_resnet18")
     ap.add_argument("--tile", type=int, default=0, help="override COMBO_TUNE_TILE_COLS")
     ap.add_argument("--swizzle", type=int, default=-1, help="override COMBO_TUNE_XCD_SWIZZLE")
+    ap.add_argument("--kernel", type=int, default=-1, help="override COMBO_TUNE_KERNEL")
+    ap.add_argument("--slab-cols", type=int, default=-1, help="override COMBO_TUNE_SLAB_COLS")
+    ap.add_argument("--fused-mode", type=int, default=-1, help="override COMBO_TUNE_FUSED_MODE")
+    ap.add_argument("--replicas", type=int, default=-1,
+                    help="override R (0 turns the round into a plain copy of known size: the "
+                         "calibration kernel for the HBM byte counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -97,7 +103,16 @@ def main():
         combo.tune(combo.TUNE_TILE_COLS, args.tile)
     if args.swizzle >= 0:
         combo.tune(combo.TUNE_XCD_SWIZZLE, args.swizzle)
+    if args.kernel >= 0:
+        combo.tune(combo.TUNE_KERNEL, args.kernel)
+    if args.slab_cols >= 0:
+        combo.tune(combo.TUNE_SLAB_COLS, args.slab_cols)
+    if args.fused_mode >= 0:
+        combo.tune(combo.TUNE_FUSED_MODE, args.fused_mode)
     wl = combo.workloads.WORKLOADS[args.workload]
+    if args.replicas >= 0:
+        import dataclasses
+        wl = dataclasses.replace(wl, R=args.replicas, name=f"{wl.name}_R{args.replicas}")
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
@@ -162,7 +177,10 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": wl.name, "N": wl.N, "P": wl.P, "S": wl.S, "R": wl.R,
-                   "fused_local_step": wl.fused, "tile_cols": combo.get_tune(combo.TUNE_TILE_COLS),
+                   "fused_local_step": wl.fused, "kernel": combo.get_tune(combo.TUNE_KERNEL),
+                   "slab_cols": combo.get_tune(combo.TUNE_SLAB_COLS),
+                   "fused_mode": combo.get_tune(combo.TUNE_FUSED_MODE),
+                   "tile_cols": combo.get_tune(combo.TUNE_TILE_COLS),
                    "xcd_swizzle": combo.get_tune(combo.TUNE_XCD_SWIZZLE)},
         "effective_hbm_gbs": alg_bytes / (wall / args.steps) / 1e9,
         "effective_hbm_pct_of_peak": 100.0 * alg_bytes / (wall / args.steps) / 1e9 / HBM_PEAK_GBS,

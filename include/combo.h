@@ -106,9 +106,10 @@ int combo_segment_gossip_round(float* d_dst, const float* d_src, int64_t ld,
  * difference), and only then Eq. (3) is applied to the stepped parameters x' exactly as
  * in combo_segment_gossip_round.
  *
- *   d_src   in/out, device, float32[N][ld]: on return it holds the stepped parameters x'
- *           (the step is applied in place, which is also what makes every reader see
- *           post-update values).
+ *   d_src   in/out, device, float32[N][ld]: the pre-update parameters x.  On return its
+ *           contents are x or x', unspecified which (the fused kernel forms x' on the
+ *           fly and leaves d_src alone; the two-pass fallback steps d_src in place).
+ *           Callers ping-pong the buffers, so the old front buffer is dead either way.
  *   d_grad  in, device, float32[N][ld], same pitch; not modified.
  * Errors: as combo_segment_gossip_round, plus COMBO_EINVAL for a NULL d_grad and
  * COMBO_EALIAS if d_grad overlaps d_src or d_dst.
@@ -120,16 +121,28 @@ int combo_local_sgd_then_gossip(float* d_dst, float* d_src, const float* d_grad,
 
 /*
  * Performance knobs (process-global, host side only; results never depend on them).
- *   COMBO_TUNE_TILE_COLS   columns of one worker handled by one workgroup:
- *                          1024, 2048 or 4096 (256 threads x 1, 2 or 4 float4 each)
- *   COMBO_TUNE_XCD_SWIZZLE 1: consecutive workgroups on one XCD are the N workers of
- *                          one column tile (peer rows are re-read from that XCD's L2);
- *                          0: plain worker-major order
- *   COMBO_TUNE_FUSED_MODE  0: in-place step kernel then the round (what
- *                          combo_local_sgd_then_gossip documents); no other mode yet
+ *   COMBO_TUNE_KERNEL      0: automatic (LDS-slab kernel when the buffers are 16-byte
+ *                          aligned, ld % 4 == 0 and N rows of a 64-column strip fit in
+ *                          64 KiB of LDS, else the row-tile kernel); 1: always the
+ *                          row-tile kernel; 2: same as 0
+ *   COMBO_TUNE_SLAB_COLS   strip width of the slab kernel: 0 = automatic, or a power of
+ *                          two in [64, 1024] (ignored if that slab does not fit in LDS)
+ *   COMBO_TUNE_TILE_COLS   row-tile kernel: columns of one worker handled by one
+ *                          workgroup: 1024, 2048 or 4096
+ *   COMBO_TUNE_XCD_SWIZZLE row-tile kernel: 1: consecutive workgroups on one XCD are the
+ *                          N workers of one column tile (peer rows are re-read from that
+ *                          XCD's L2); 0: plain worker-major order
+ *   COMBO_TUNE_FUSED_MODE  combo_local_sgd_then_gossip: 0: fold the step into the slab
+ *                          kernel when that kernel is used; 1: always two passes
  * Returns COMBO_OK or COMBO_EINVAL for an unknown key or unsupported value.
  */
-enum { COMBO_TUNE_TILE_COLS = 0, COMBO_TUNE_XCD_SWIZZLE = 1, COMBO_TUNE_FUSED_MODE = 2 };
+enum {
+    COMBO_TUNE_TILE_COLS = 0,
+    COMBO_TUNE_XCD_SWIZZLE = 1,
+    COMBO_TUNE_FUSED_MODE = 2,
+    COMBO_TUNE_KERNEL = 3,
+    COMBO_TUNE_SLAB_COLS = 4
+};
 int combo_tune(int key, int value);
 int combo_get_tune(int key); /* current value, or COMBO_EINVAL */
 

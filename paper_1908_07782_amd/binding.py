@@ -10,6 +10,8 @@ LIB_PATH = os.path.join(HERE, "libcombo.so")
 TUNE_TILE_COLS = 0
 TUNE_XCD_SWIZZLE = 1
 TUNE_FUSED_MODE = 2
+TUNE_KERNEL = 3
+TUNE_SLAB_COLS = 4
 
 EXPORTS = ("combo_make_peer_table", "combo_segment_gossip_round", "combo_local_sgd_then_gossip",
            "combo_tune", "combo_get_tune", "combo_strerror")

@@ -11,6 +11,8 @@ namespace {
 std::atomic<int> g_tile_cols{2048};
 std::atomic<int> g_swizzle{1};
 std::atomic<int> g_fused_mode{0};
+std::atomic<int> g_kernel{0};
+std::atomic<int> g_slab_cols{0};
 
 bool overlaps(const void* a, uint64_t a_bytes, const void* b, uint64_t b_bytes) {
     const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
@@ -30,16 +32,20 @@ int check_round_args(const float* dst, const float* src, int64_t ld, const int32
     return COMBO_OK;
 }
 
-int enqueue_round(float* dst, const float* src, int64_t ld, const int32_t* peers,
-                  const float* dsz, int32_t N, int64_t P, int32_t S, int32_t R, hipStream_t st) {
+// Enqueue one aggregation round.  grad != nullptr: the local step is fused into the
+// round (only possible with the slab kernel); the caller has checked that with
+// fused_in_round().
+int enqueue_round(float* dst, const float* src, const float* grad, float lr, int64_t ld,
+                  const int32_t* peers, const float* dsz, int32_t N, int64_t P, int32_t S,
+                  int32_t R, int slab_cols, hipStream_t st) {
     const int tile_cols = g_tile_cols.load();
     const bool swizzle = g_swizzle.load() != 0;
-    if (combo::round_grid_size(N, P, tile_cols, swizzle) == 0) return COMBO_ERANGE;
     combo::RoundArgs a;
     a.dst = dst;
     a.src = src;
     a.peers = peers;
     a.dsz = dsz;
+    a.grad = grad;
     a.ld = ld;
     a.P = P;
     a.L = P / S;
@@ -50,8 +56,23 @@ int enqueue_round(float* dst, const float* src, int64_t ld, const int32_t* peers
     a.swizzle = swizzle ? 1 : 0;
     a.p32 = P < (int64_t)0x100000000ll ? 1 : 0;
     a.inv = 1.0f / (float)(R + 1);
+    a.lr = lr;
+    if (slab_cols)
+        return combo::launch_round_slab(a, slab_cols, st) == hipSuccess ? COMBO_OK : COMBO_EHIP;
+    if (combo::round_grid_size(N, P, tile_cols, swizzle) == 0) return COMBO_ERANGE;
     const bool vec = aligned16(dst) && aligned16(src) && (ld % 4 == 0);
     return combo::launch_round(a, tile_cols, vec, st) == hipSuccess ? COMBO_OK : COMBO_EHIP;
+}
+
+// Strip width if this round runs in the slab kernel, 0 if it runs in the row-tile kernel.
+int slab_cols_for(const float* dst, const float* src, const float* grad, int64_t ld, int32_t N,
+                  int64_t P, int32_t R) {
+    if (g_kernel.load() == 1) return 0;
+    if (!(aligned16(dst) && aligned16(src) && aligned16(grad) && ld % 4 == 0)) return 0;
+    const int W = combo::slab_strip_cols(N, R, g_slab_cols.load());
+    if (W == 0) return 0;
+    if (((uint64_t)P + (uint64_t)W - 1) / (uint64_t)W > 0x7FFFFFFFull) return 0;
+    return W;
 }
 
 }  // namespace
@@ -74,7 +95,8 @@ int combo_segment_gossip_round(float* d_dst, const float* d_src, int64_t ld,
                                int64_t P, int32_t S, int32_t R, void* stream) {
     const int rc = check_round_args(d_dst, d_src, ld, d_peers, N, P, S, R);
     if (rc != COMBO_OK) return rc;
-    return enqueue_round(d_dst, d_src, ld, d_peers, d_dataset_sizes, N, P, S, R,
+    const int W = slab_cols_for(d_dst, d_src, nullptr, ld, N, P, R);
+    return enqueue_round(d_dst, d_src, nullptr, 0.0f, ld, d_peers, d_dataset_sizes, N, P, S, R, W,
                          (hipStream_t)stream);
 }
 
@@ -87,13 +109,18 @@ int combo_local_sgd_then_gossip(float* d_dst, float* d_src, const float* d_grad,
     const uint64_t bytes = (uint64_t)N * (uint64_t)ld * sizeof(float);
     if (overlaps(d_grad, bytes, d_src, bytes) || overlaps(d_grad, bytes, d_dst, bytes))
         return COMBO_EALIAS;
-    if (combo::round_grid_size(N, P, g_tile_cols.load(), g_swizzle.load() != 0) == 0 ||
+    const int W = slab_cols_for(d_dst, d_src, d_grad, ld, N, P, R);
+    if (W != 0 && g_fused_mode.load() == 0)   // step folded into the slab fill; d_src untouched
+        return enqueue_round(d_dst, d_src, d_grad, lr, ld, d_peers, d_dataset_sizes, N, P, S, R, W,
+                             (hipStream_t)stream);
+    // two passes: step every row in place, then the plain round on the stepped buffer
+    if ((W == 0 && combo::round_grid_size(N, P, g_tile_cols.load(), g_swizzle.load() != 0) == 0) ||
         combo::round_grid_size(N, P, 4096, false) == 0)
         return COMBO_ERANGE;
     const bool vec = aligned16(d_src) && aligned16(d_grad) && (ld % 4 == 0);
     if (combo::launch_sgd_step(d_src, d_grad, lr, ld, N, P, vec, (hipStream_t)stream) != hipSuccess)
         return COMBO_EHIP;
-    return enqueue_round(d_dst, d_src, ld, d_peers, d_dataset_sizes, N, P, S, R,
+    return enqueue_round(d_dst, d_src, nullptr, 0.0f, ld, d_peers, d_dataset_sizes, N, P, S, R, W,
                          (hipStream_t)stream);
 }
 
@@ -108,8 +135,17 @@ int combo_tune(int key, int value) {
             g_swizzle.store(value);
             return COMBO_OK;
         case COMBO_TUNE_FUSED_MODE:
-            if (value != 0) return COMBO_EINVAL;
+            if (value != 0 && value != 1) return COMBO_EINVAL;
             g_fused_mode.store(value);
+            return COMBO_OK;
+        case COMBO_TUNE_KERNEL:
+            if (value < 0 || value > 2) return COMBO_EINVAL;
+            g_kernel.store(value);
+            return COMBO_OK;
+        case COMBO_TUNE_SLAB_COLS:
+            if (value != 0 && !(value >= 64 && value <= 1024 && (value & (value - 1)) == 0))
+                return COMBO_EINVAL;
+            g_slab_cols.store(value);
             return COMBO_OK;
         default:
             return COMBO_EINVAL;
@@ -121,6 +157,8 @@ int combo_get_tune(int key) {
         case COMBO_TUNE_TILE_COLS: return g_tile_cols.load();
         case COMBO_TUNE_XCD_SWIZZLE: return g_swizzle.load();
         case COMBO_TUNE_FUSED_MODE: return g_fused_mode.load();
+        case COMBO_TUNE_KERNEL: return g_kernel.load();
+        case COMBO_TUNE_SLAB_COLS: return g_slab_cols.load();
         default: return COMBO_EINVAL;
     }
 }

@@ -17,6 +17,7 @@ struct RoundArgs {
     const float* src;
     const int32_t* peers;
     const float* dsz;        // dataset sizes |D_j| or nullptr (uniform weights)
+    const float* grad;       // gradients for the fused local step, or nullptr
     int64_t ld;              // row pitch in elements
     int64_t P;               // parameters per worker
     int64_t L;               // floor(P / S): length of every segment but the last
@@ -25,6 +26,7 @@ struct RoundArgs {
     int32_t swizzle;         // 1: XCD-aware workgroup order
     int32_t p32;             // 1: P < 2^32, segment lookup may divide in 32 bits
     float inv;               // 1.0f / (float)(R + 1)
+    float lr;                // learning rate of the fused local step
 };
 
 // launchers (defined in gossip_round.hip / peer_table.hip); return hipGetLastError()
@@ -33,6 +35,11 @@ hipError_t launch_sgd_step(float* x, const float* g, float lr, int64_t ld, int32
                            bool vec, hipStream_t st);
 hipError_t launch_peer_table(int32_t* peers, int32_t N, int32_t S, int32_t R, uint64_t seed,
                              uint64_t round, hipStream_t st);
+
+// Slab kernel: one workgroup stages all N rows of a strip of `strip_cols` columns in
+// LDS.  slab_strip_cols() picks the strip width for N workers (0: does not fit in LDS).
+int slab_strip_cols(int32_t N, int32_t R, int requested);
+hipError_t launch_round_slab(const RoundArgs& a, int strip_cols, hipStream_t st);
 
 // number of workgroups launch_round would use, or 0 if that exceeds the grid limit
 uint64_t round_grid_size(int32_t N, int64_t P, int tile_cols, bool swizzle);

@@ -23,51 +23,10 @@
 //
 // This is a streaming gather, not a contraction: no MFMA.
 #include "combo_internal.h"
+#include "round_device.h"
 
 namespace combo {
 namespace {
-
-typedef float v4f __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ v4f load4(const float* p) { return *reinterpret_cast<const v4f*>(p); }
-
-__device__ __forceinline__ void store4_stream(float* p, v4f v) {
-    __builtin_nontemporal_store(v, reinterpret_cast<v4f*>(p));
-}
-
-// segment of column e: floor(e / L), the last segment also owning the remainder
-__device__ __forceinline__ int32_t segment_of(int64_t e, const RoundArgs& a) {
-    uint64_t q;
-    if (a.p32) q = (uint32_t)e / (uint32_t)a.L;
-    else q = (uint64_t)e / (uint64_t)a.L;
-    return q >= (uint64_t)a.S ? a.S - 1 : (int32_t)q;
-}
-
-// one element, any segment: used for boundary tiles, ragged ends and unaligned buffers
-template <bool WEIGHTED>
-__device__ __forceinline__ void average_element(const RoundArgs& a, int32_t w, int64_t e) {
-    const int32_t s = segment_of(e, a);
-    const int32_t* pl = a.peers + ((size_t)w * (size_t)a.S + (size_t)s) * (size_t)a.R;
-    const float own = a.src[(size_t)w * (size_t)a.ld + (size_t)e];
-    float out;
-    if (!WEIGHTED) {
-        float acc = own;
-        for (int32_t j = 0; j < a.R; ++j)
-            acc = __fadd_rn(acc, a.src[(size_t)pl[j] * (size_t)a.ld + (size_t)e]);
-        out = __fmul_rn(acc, a.inv);
-    } else {
-        float den = a.dsz[w];
-        float num = __fmul_rn(den, own);
-        for (int32_t j = 0; j < a.R; ++j) {
-            const int32_t p = pl[j];
-            const float dp = a.dsz[p];
-            den = __fadd_rn(den, dp);
-            num = __fadd_rn(num, __fmul_rn(dp, a.src[(size_t)p * (size_t)a.ld + (size_t)e]));
-        }
-        out = __fdiv_rn(num, den);
-    }
-    a.dst[(size_t)w * (size_t)a.ld + (size_t)e] = out;
-}
 
 // RT >= 0: replica count known at compile time (loads fully unrolled); RT < 0: a.R.
 // VPT: 128-bit vectors per thread; the tile is kThreads*VPT*4 columns.
@@ -166,7 +125,7 @@ __global__ __launch_bounds__(kThreads) void gossip_round_kernel(const RoundArgs 
                     }
                     store4_stream(out_row + col, y);
                 } else {
-                    for (int64_t e = col; e < col_end; ++e) average_element<WEIGHTED>(a, w, e);
+                    for (int64_t e = col; e < col_end; ++e) average_element<WEIGHTED, false>(a, w, e);
                 }
             }
         } else {
@@ -218,14 +177,14 @@ __global__ __launch_bounds__(kThreads) void gossip_round_kernel(const RoundArgs 
                     }
                     store4_stream(out_row + col, y);
                 } else {
-                    for (int64_t e = col; e < col_end; ++e) average_element<WEIGHTED>(a, w, e);
+                    for (int64_t e = col; e < col_end; ++e) average_element<WEIGHTED, false>(a, w, e);
                 }
             }
         }
     } else {
         // ---- boundary tile or unaligned buffers: one element per lane, coalesced ----
         for (int64_t e = col_begin + threadIdx.x; e < col_end; e += kThreads)
-            average_element<WEIGHTED>(a, w, e);
+            average_element<WEIGHTED, false>(a, w, e);
     }
 }
 

@@ -1,0 +1,174 @@
+// Gather-average round, LDS-slab form: Eq. (3) / Eq. (4) of the segmented-gossip paper
+// with every front-buffer element fetched exactly once.
+//
+// One workgroup owns a strip of `W` consecutive columns of ALL N workers.  It first
+// copies the N x W slab of the front buffer into LDS (each wave instruction moves whole
+// 128-bit words of one row: fully coalesced), together with the strip's peer list
+// peers[.][s][.] and, for weighted rounds, the dataset sizes.  After one barrier every
+// output element is formed from LDS: own value, then the R providers in table order,
+// then the scale - the same fixed order as the row-tile kernel - and streamed to the
+// back buffer with non-temporal 128-bit stores.  HBM and L2 see one read and one write
+// per element whatever R is; the R+1 reads per output are LDS reads.
+//
+// With the local step fused in, the slab is filled with x - lr*g (gradient read once,
+// product rounded before the difference), so peers are served post-update values as
+// Sec. 4.1 requires, and the front buffer itself is left untouched.
+//
+// A strip that contains a segment boundary or the ragged end of the row (at most S
+// strips per round) falls back to per-element evaluation from global memory.
+#include "combo_internal.h"
+#include "round_device.h"
+
+namespace combo {
+namespace {
+
+constexpr int kBatch = 8;   // 128-bit loads kept in flight per thread while filling the slab
+
+template <int RT, bool WEIGHTED, bool FUSED>
+__global__ __launch_bounds__(kThreads) void gossip_slab_kernel(const RoundArgs a, const int W) {
+    extern __shared__ v4f lds[];
+    const int32_t R = RT >= 0 ? RT : a.R;
+    const int32_t N = a.N;
+    const int W4 = W >> 2;                       // 128-bit words per row of the strip
+    const int w4_shift = 31 - __clz(W4);         // W4 is a power of two
+    const int total4 = N * W4;
+
+    v4f* slab = lds;                                                   // [N][W4]
+    int32_t* lds_peers = reinterpret_cast<int32_t*>(lds + total4);     // [N][R]
+    float* lds_d = reinterpret_cast<float*>(lds_peers + (size_t)N * (size_t)R);   // [N]
+
+    const int64_t col0 = (int64_t)blockIdx.x * W;
+    const int64_t col_end = col0 + W < a.P ? col0 + W : a.P;
+    const int32_t s0 = segment_of(col0, a);
+    const int64_t seg_end = (s0 == a.S - 1) ? a.P : (int64_t)(s0 + 1) * a.L;
+
+    if (col_end - col0 == W && col_end <= seg_end) {
+        // ---- fill: peer list, weights, then the slab --------------------------------
+        for (int i = threadIdx.x; R > 0 && i < N * R; i += kThreads) {
+            const int w = i / (R > 0 ? R : 1);
+            const int j = i - w * R;
+            lds_peers[i] = a.peers[((size_t)w * (size_t)a.S + (size_t)s0) * (size_t)R + (size_t)j];
+        }
+        if (WEIGHTED)
+            for (int i = threadIdx.x; i < N; i += kThreads) lds_d[i] = a.dsz[i];
+
+        for (int base = 0; base < total4; base += kThreads * kBatch) {
+            v4f x[kBatch], g[kBatch];
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                const int idx = base + u * kThreads + (int)threadIdx.x;
+                if (idx < total4) {
+                    const int row = idx >> w4_shift;
+                    const int c4 = idx & (W4 - 1);
+                    const size_t off = (size_t)row * (size_t)a.ld + (size_t)col0 + (size_t)c4 * 4;
+                    x[u] = load4(a.src + off);
+                    if (FUSED) g[u] = load4(a.grad + off);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                const int idx = base + u * kThreads + (int)threadIdx.x;
+                if (idx < total4) slab[idx] = FUSED ? sgd_step4(x[u], a.lr, g[u]) : x[u];
+            }
+        }
+        __syncthreads();
+
+        // ---- aggregate from LDS ---------------------------------------------------
+        for (int idx = threadIdx.x; idx < total4; idx += kThreads) {
+            const int w = idx >> w4_shift;
+            const int c4 = idx & (W4 - 1);
+            const int32_t* pl = lds_peers + w * R;
+            v4f acc = slab[idx];
+            v4f y;
+            if (!WEIGHTED) {
+                if (RT >= 0) {
+#pragma unroll
+                    for (int j = 0; j < (RT >= 0 ? RT : 0); ++j)
+                        acc = add4(acc, slab[(pl[j] << w4_shift) + c4]);
+                } else {
+                    for (int j = 0; j < R; ++j) acc = add4(acc, slab[(pl[j] << w4_shift) + c4]);
+                }
+                y = scale4(a.inv, acc);
+            } else {
+                float den = lds_d[w];
+                acc = scale4(den, acc);
+                for (int j = 0; j < R; ++j) {
+                    const int p = pl[j];
+                    const float dp = lds_d[p];
+                    den = __fadd_rn(den, dp);
+                    acc = add4(acc, scale4(dp, slab[(p << w4_shift) + c4]));
+                }
+                y = div4(acc, den);
+            }
+            store4_stream(a.dst + (size_t)w * (size_t)a.ld + (size_t)col0 + (size_t)c4 * 4, y);
+        }
+    } else {
+        // ---- boundary or ragged strip: element by element from global memory --------
+        const int width = (int)(col_end - col0);
+        const int total = N * width;
+        for (int idx = threadIdx.x; idx < total; idx += kThreads) {
+            const int w = idx / width;
+            const int64_t e = col0 + (idx - w * width);
+            average_element<WEIGHTED, FUSED>(a, w, e);
+        }
+    }
+}
+
+size_t slab_lds_bytes(int32_t N, int32_t R, int W) {
+    return (size_t)N * (size_t)W * 4 + (size_t)N * (size_t)R * 4 + (size_t)N * 4;
+}
+
+template <int RT>
+hipError_t launch_rt(const RoundArgs& a, int W, uint32_t grid, size_t lds, hipStream_t st) {
+    const bool weighted = a.dsz != nullptr, fused = a.grad != nullptr;
+#define COMBO_SLAB_LAUNCH(WT, FU)                                                             \
+    hipLaunchKernelGGL((gossip_slab_kernel<RT, WT, FU>), dim3(grid), dim3(kThreads), lds, st, a, W)
+    if (weighted) {
+        if (fused) COMBO_SLAB_LAUNCH(true, true);
+        else COMBO_SLAB_LAUNCH(true, false);
+    } else {
+        if (fused) COMBO_SLAB_LAUNCH(false, true);
+        else COMBO_SLAB_LAUNCH(false, false);
+    }
+#undef COMBO_SLAB_LAUNCH
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// Widest power-of-two strip in [64, 1024] columns whose slab (plus peer list and
+// weights) stays within 64 KiB of LDS and, when possible, within about 40 KiB so that
+// several workgroups share a compute unit.  `requested` != 0 forces a width if it fits.
+int slab_strip_cols(int32_t N, int32_t R, int requested) {
+    const size_t kLimit = 64 * 1024;
+    if (requested) {
+        const bool pow2 = (requested & (requested - 1)) == 0;
+        if (pow2 && requested >= 64 && requested <= 1024 &&
+            slab_lds_bytes(N, R, requested) <= kLimit)
+            return requested;
+    }
+    for (int W = 1024; W >= 64; W >>= 1)
+        if (slab_lds_bytes(N, R, W) <= 40 * 1024) return W;
+    return slab_lds_bytes(N, R, 64) <= kLimit ? 64 : 0;
+}
+
+hipError_t launch_round_slab(const RoundArgs& a, int W, hipStream_t st) {
+    const uint64_t strips = ((uint64_t)a.P + (uint64_t)W - 1) / (uint64_t)W;
+    if (strips > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    const size_t lds = slab_lds_bytes(a.N, a.R, W);
+    const uint32_t grid = (uint32_t)strips;
+    switch (a.R) {
+        case 0: return launch_rt<0>(a, W, grid, lds, st);
+        case 1: return launch_rt<1>(a, W, grid, lds, st);
+        case 2: return launch_rt<2>(a, W, grid, lds, st);
+        case 3: return launch_rt<3>(a, W, grid, lds, st);
+        case 4: return launch_rt<4>(a, W, grid, lds, st);
+        case 5: return launch_rt<5>(a, W, grid, lds, st);
+        case 6: return launch_rt<6>(a, W, grid, lds, st);
+        case 7: return launch_rt<7>(a, W, grid, lds, st);
+        case 8: return launch_rt<8>(a, W, grid, lds, st);
+        default: return launch_rt<-1>(a, W, grid, lds, st);
+    }
+}
+
+}  // namespace combo

@@ -1,0 +1,102 @@
+// Device helpers shared by the aggregation kernels (HIP path only).
+#ifndef COMBO_ROUND_DEVICE_H_
+#define COMBO_ROUND_DEVICE_H_
+
+#include "combo_internal.h"
+
+namespace combo {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ v4f load4(const float* p) { return *reinterpret_cast<const v4f*>(p); }
+
+__device__ __forceinline__ void store4_stream(float* p, v4f v) {
+    __builtin_nontemporal_store(v, reinterpret_cast<v4f*>(p));
+}
+
+// x - lr*g with the product rounded before the difference (one SGD step, Sec. 4.1 step 1)
+__device__ __forceinline__ float sgd_step(float x, float lr, float g) {
+    return __fsub_rn(x, __fmul_rn(lr, g));
+}
+
+__device__ __forceinline__ v4f sgd_step4(v4f x, float lr, v4f g) {
+    v4f y;
+    y.x = sgd_step(x.x, lr, g.x);
+    y.y = sgd_step(x.y, lr, g.y);
+    y.z = sgd_step(x.z, lr, g.z);
+    y.w = sgd_step(x.w, lr, g.w);
+    return y;
+}
+
+__device__ __forceinline__ v4f add4(v4f a, v4f b) {
+    v4f y;
+    y.x = __fadd_rn(a.x, b.x);
+    y.y = __fadd_rn(a.y, b.y);
+    y.z = __fadd_rn(a.z, b.z);
+    y.w = __fadd_rn(a.w, b.w);
+    return y;
+}
+
+__device__ __forceinline__ v4f scale4(float s, v4f a) {
+    v4f y;
+    y.x = __fmul_rn(s, a.x);
+    y.y = __fmul_rn(s, a.y);
+    y.z = __fmul_rn(s, a.z);
+    y.w = __fmul_rn(s, a.w);
+    return y;
+}
+
+__device__ __forceinline__ v4f div4(v4f a, float d) {
+    v4f y;
+    y.x = __fdiv_rn(a.x, d);
+    y.y = __fdiv_rn(a.y, d);
+    y.z = __fdiv_rn(a.z, d);
+    y.w = __fdiv_rn(a.w, d);
+    return y;
+}
+
+// segment of column e: floor(e / L), the last segment also owning the remainder (Eq. 1)
+__device__ __forceinline__ int32_t segment_of(int64_t e, const RoundArgs& a) {
+    uint64_t q;
+    if (a.p32) q = (uint32_t)e / (uint32_t)a.L;
+    else q = (uint64_t)e / (uint64_t)a.L;
+    return q >= (uint64_t)a.S ? a.S - 1 : (int32_t)q;
+}
+
+// pre-aggregation value of worker `row` at column e: the stored parameter, or, when the
+// local step is fused in, the parameter after one SGD step
+template <bool FUSED>
+__device__ __forceinline__ float served_value(const RoundArgs& a, int32_t row, int64_t e) {
+    const size_t k = (size_t)row * (size_t)a.ld + (size_t)e;
+    if (FUSED) return sgd_step(a.src[k], a.lr, a.grad[k]);
+    return a.src[k];
+}
+
+// Eq. (3) for one element of any segment: used for tiles that contain a segment
+// boundary, ragged row ends and unaligned buffers
+template <bool WEIGHTED, bool FUSED>
+__device__ __forceinline__ void average_element(const RoundArgs& a, int32_t w, int64_t e) {
+    const int32_t s = segment_of(e, a);
+    const int32_t* pl = a.peers + ((size_t)w * (size_t)a.S + (size_t)s) * (size_t)a.R;
+    const float own = served_value<FUSED>(a, w, e);
+    float out;
+    if (!WEIGHTED) {
+        float acc = own;
+        for (int32_t j = 0; j < a.R; ++j) acc = __fadd_rn(acc, served_value<FUSED>(a, pl[j], e));
+        out = __fmul_rn(acc, a.inv);
+    } else {
+        float den = a.dsz[w];
+        float num = __fmul_rn(den, own);
+        for (int32_t j = 0; j < a.R; ++j) {
+            const int32_t p = pl[j];
+            const float dp = a.dsz[p];
+            den = __fadd_rn(den, dp);
+            num = __fadd_rn(num, __fmul_rn(dp, served_value<FUSED>(a, p, e)));
+        }
+        out = __fdiv_rn(num, den);
+    }
+    a.dst[(size_t)w * (size_t)a.ld + (size_t)e] = out;
+}
+
+}  // namespace combo
+#endif

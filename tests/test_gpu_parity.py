@@ -23,9 +23,27 @@ def combo():
     return c
 
 
+def set_variant(combo, variant):
+    """variant: ("slab", strip columns or 0 for automatic) or ("tile", tile columns)."""
+    kind, cols = variant
+    if kind == "slab":
+        combo.tune(combo.TUNE_KERNEL, 0)
+        combo.tune(combo.TUNE_SLAB_COLS, cols)
+    else:
+        combo.tune(combo.TUNE_KERNEL, 1)
+        combo.tune(combo.TUNE_TILE_COLS, cols)
+
+
+VARIANTS = [("slab", 0), ("slab", 64), ("slab", 256), ("slab", 1024),
+            ("tile", 1024), ("tile", 2048), ("tile", 4096)]
+
+
 @pytest.fixture(autouse=True)
 def _default_tuning(combo):
     yield
+    combo.tune(combo.TUNE_KERNEL, 0)
+    combo.tune(combo.TUNE_SLAB_COLS, 0)
+    combo.tune(combo.TUNE_FUSED_MODE, 0)
     combo.tune(combo.TUNE_TILE_COLS, 2048)
     combo.tune(combo.TUNE_XCD_SWIZZLE, 1)
 
@@ -127,16 +145,18 @@ SMALL_SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("N,P,S,R", SMALL_SHAPES)
-@pytest.mark.parametrize("tile", [1024, 2048, 4096])
-def test_round_matches_oracle_small(combo, ref, N, P, S, R, tile):
-    combo.tune(combo.TUNE_TILE_COLS, tile)
+@pytest.mark.parametrize("N,P,S,R", SMALL_SHAPES + [(100, 20_003, 7, 3), (250, 3_001, 3, 5),
+                                                    (300, 2_000, 2, 2)])
+@pytest.mark.parametrize("variant", VARIANTS, ids=lambda v: f"{v[0]}{v[1]}")
+def test_round_matches_oracle_small(combo, ref, N, P, S, R, variant):
+    set_variant(combo, variant)
     got, want, _, _ = run_small(combo, ref, N, P, S, R)
-    assert_params_match(got, want, f"N{N} P{P} S{S} R{R} tile{tile}")
+    assert_params_match(got, want, f"N{N} P{P} S{S} R{R} {variant}")
 
 
 @pytest.mark.parametrize("N,P,S,R", [(5, 10_007, 7, 3), (32, 40_000, 32, 4), (12, 20_000, 5, 11)])
 def test_round_plain_workgroup_order(combo, ref, N, P, S, R):
+    combo.tune(combo.TUNE_KERNEL, 1)
     combo.tune(combo.TUNE_XCD_SWIZZLE, 0)
     got, want, _, _ = run_small(combo, ref, N, P, S, R)
     assert_params_match(got, want)
@@ -144,7 +164,10 @@ def test_round_plain_workgroup_order(combo, ref, N, P, S, R):
 
 @pytest.mark.parametrize("N,P,S,R", [(5, 10_007, 7, 3), (8, 40_001, 3, 4), (6, 130, 130, 1),
                                      (16, 30_011, 4, 9), (9, 5_000, 2, 0), (32, 70_000, 32, 4)])
-def test_round_dataset_size_weights(combo, ref, N, P, S, R):
+@pytest.mark.parametrize("variant", [("slab", 0), ("slab", 128), ("tile", 2048)],
+                         ids=lambda v: f"{v[0]}{v[1]}")
+def test_round_dataset_size_weights(combo, ref, N, P, S, R, variant):
+    set_variant(combo, variant)
     got, want, _, _ = run_small(combo, ref, N, P, S, R, weighted=True, seed=3)
     assert_params_match(got, want)
 
@@ -249,10 +272,13 @@ def test_c1_tiny_full(combo, ref):
     assert bool(torch.isnan(arena[cur, :, wl.P:]).all()) if wl.ld > wl.P else True
 
 
-def test_c4_prime_fused_full_three_rounds(combo, ref):
+@pytest.mark.parametrize("mode", ["fused_slab", "two_pass_slab", "two_pass_tile"])
+def test_c4_prime_fused_full_three_rounds(combo, ref, mode):
     """N=100, P=1,000,003 (prime), S=7, R=3, x -= 0.01*g then gossip; full-size
     elementwise comparison over 3 of the 20 rounds (all 20 are covered on windows)."""
     wl = combo.workloads.WORKLOADS["c4_prime_fused"]
+    combo.tune(combo.TUNE_FUSED_MODE, 0 if mode == "fused_slab" else 1)
+    combo.tune(combo.TUNE_KERNEL, 1 if mode == "two_pass_tile" else 0)
     arena = make_arena(wl)
     combo.workloads.fill_params(arena[0], wl)
     grads = torch.zeros((wl.N, wl.ld), dtype=torch.float32, device="cuda")
@@ -287,14 +313,14 @@ def test_c4_prime_fused_all_rounds_on_windows(combo, ref):
 
 
 @pytest.mark.parametrize("name", ["c2_resnet18", "c3_resnet50", "c5_bertlarge"])
-@pytest.mark.parametrize("tile", [2048])
-def test_full_size_workloads_on_sampled_windows(combo, ref, name, tile):
+@pytest.mark.parametrize("variant", [("slab", 0), ("tile", 2048)], ids=lambda v: f"{v[0]}{v[1]}")
+def test_full_size_workloads_on_sampled_windows(combo, ref, name, variant):
     """Full-size arena, all rounds, in the launch configuration the benchmark times;
     compared on column windows that the oracle recomputes round by round (an output
     column depends only on the same input column, so a window of the full run equals the
     run on the window)."""
     wl = combo.workloads.WORKLOADS[name]
-    combo.tune(combo.TUNE_TILE_COLS, tile)
+    set_variant(combo, variant)
     arena = make_arena(wl)
     combo.workloads.fill_params(arena[0], wl)
     wins = sample_windows(wl)
@@ -325,7 +351,11 @@ def test_c2_resnet18_full_one_round_elementwise(combo, ref):
     assert_params_match(arena[cur, :, :wl.P].cpu().numpy(), want, "c2 full round")
 
 
-def test_fused_small_and_aliasing_contract(combo, ref):
+@pytest.mark.parametrize("mode,weighted", [("fused_slab", False), ("fused_slab", True),
+                                           ("two_pass_slab", False), ("two_pass_tile", True)])
+def test_fused_small_and_aliasing_contract(combo, ref, mode, weighted):
+    combo.tune(combo.TUNE_FUSED_MODE, 0 if mode == "fused_slab" else 1)
+    combo.tune(combo.TUNE_KERNEL, 1 if mode == "two_pass_tile" else 0)
     N, P, S, R, lr = 6, 10_007, 7, 3, 0.01
     rng = np.random.default_rng(5)
     Xh = rng.uniform(-0.1, 0.1, (N, P)).astype(np.float32)
@@ -335,14 +365,17 @@ def test_fused_small_and_aliasing_contract(combo, ref):
     buf[0, :, :P] = torch.from_numpy(Xh).cuda()
     buf[2, :, :P] = torch.from_numpy(Gh).cuda()
     peers = device_table(combo, N, S, R, 0, 0)
-    combo.local_sgd_then_gossip(buf[1], buf[0], buf[2], lr, peers, P, S, R)
+    d = combo.workloads.dataset_sizes(N, 1, "cuda") if weighted else None
+    combo.local_sgd_then_gossip(buf[1], buf[0], buf[2], lr, peers, P, S, R, dataset_sizes=d)
     torch.cuda.synchronize()
     ph = ref.make_peer_table(N, S, R, 0, 0)
     Xs = Xh.copy()
-    want = ref.local_sgd_then_gossip(Xs, Gh, lr, ph, P, S, R)
+    want = ref.local_sgd_then_gossip(Xs, Gh, lr, ph, P, S, R, d=None if d is None else d.cpu().numpy())
     assert_params_match(buf[1, :, :P].cpu().numpy(), want, "fused")
-    assert_params_match(buf[0, :, :P].cpu().numpy(), Xs, "stepped front buffer")
-    assert bool(torch.isnan(buf[:2, :, P:]).all())
+    # the old front buffer holds x (fused kernel) or the stepped x' (two passes)
+    assert_params_match(buf[0, :, :P].cpu().numpy(), Xh if mode == "fused_slab" else Xs, "front buffer")
+    assert_params_match(buf[2, :, :P].cpu().numpy(), Gh, "gradients untouched")
+    assert bool(torch.isnan(buf[:, :, P:]).all())
     # overlapping buffers are refused and nothing is enqueued
     before = buf.clone()
     with pytest.raises(combo.ComboError) as e:
