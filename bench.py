@@ -35,7 +35,7 @@ def kernel_source_digest():
 def recorded_traffic(workload):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc
     summary, or None when there is none or the kernel source changed since."""
-    path = os.path.join(ROOT, "profiles", f"gossip_round_kernel_{workload}_pmc.txt")
+    path = os.path.join(ROOT, "profiles", f"gossip_slab_kernel_{workload}_pmc.txt")
     if not os.path.exists(path):
         return None
     text = open(path).read()
@@ -159,10 +159,19 @@ def main():
     wall = t1 - t0
     kern_ms = sorted(a.elapsed_time(b) for a, b in events)
     kern_avg_ms = sum(kern_ms) / len(kern_ms)
+    # (R+1) served values read + 1 written per element; the fused local step adds the
+    # read of the gradient (folded into the slab fill) or, in two passes, a read of x and
+    # g and a write of x
     alg_bytes = wl.algorithmic_bytes_per_round
     if wl.fused:
-        alg_bytes += 4 * 3 * wl.N * wl.P          # in-place step: read x, read g, write x
+        fused_in_kernel = combo.get_tune(combo.TUNE_KERNEL) != 1 and \
+            combo.get_tune(combo.TUNE_FUSED_MODE) == 0
+        alg_bytes += 4 * wl.N * wl.P * (1 if fused_in_kernel else 3)
     achieved = alg_bytes / (kern_avg_ms * 1e-3) / 1e9
+    slab = combo.get_tune(combo.TUNE_KERNEL) != 1
+    two_pass = wl.fused and (not slab or combo.get_tune(combo.TUNE_FUSED_MODE) == 1)
+    kernel_name = ("gossip_slab_kernel" if slab else "gossip_round_kernel") + \
+        (" (+ sgd_step_kernel)" if two_pass else "")
     out = {
         "metric": "gossip rounds/sec and effective HBM GB/s (% of peak) at N workers x P params",
         "value": args.steps / wall,
@@ -186,7 +195,7 @@ def main():
         "effective_hbm_pct_of_peak": 100.0 * alg_bytes / (wall / args.steps) / 1e9 / HBM_PEAK_GBS,
         "roofline": {
             "bound": "hbm",
-            "kernel": "gossip_round_kernel" + (" (+ sgd_step_kernel)" if wl.fused else ""),
+            "kernel": kernel_name,
             "achieved": achieved,
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",

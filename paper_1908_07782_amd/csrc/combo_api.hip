@@ -14,6 +14,12 @@ std::atomic<int> g_fused_mode{0};
 std::atomic<int> g_kernel{0};
 std::atomic<int> g_slab_cols{0};
 
+enum PlanKind { kPlanTile = 0, kPlanSlab = 1 };
+struct Plan {
+    PlanKind kind;
+    int cols;      // strip width for the slab kernels
+};
+
 bool overlaps(const void* a, uint64_t a_bytes, const void* b, uint64_t b_bytes) {
     const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
     return a0 < b0 + b_bytes && b0 < a0 + a_bytes;
@@ -37,7 +43,7 @@ int check_round_args(const float* dst, const float* src, int64_t ld, const int32
 // fused_in_round().
 int enqueue_round(float* dst, const float* src, const float* grad, float lr, int64_t ld,
                   const int32_t* peers, const float* dsz, int32_t N, int64_t P, int32_t S,
-                  int32_t R, int slab_cols, hipStream_t st) {
+                  int32_t R, Plan plan, hipStream_t st) {
     const int tile_cols = g_tile_cols.load();
     const bool swizzle = g_swizzle.load() != 0;
     combo::RoundArgs a;
@@ -57,22 +63,24 @@ int enqueue_round(float* dst, const float* src, const float* grad, float lr, int
     a.p32 = P < (int64_t)0x100000000ll ? 1 : 0;
     a.inv = 1.0f / (float)(R + 1);
     a.lr = lr;
-    if (slab_cols)
-        return combo::launch_round_slab(a, slab_cols, st) == hipSuccess ? COMBO_OK : COMBO_EHIP;
+    if (plan.kind == kPlanSlab)
+        return combo::launch_round_slab(a, plan.cols, st) == hipSuccess ? COMBO_OK : COMBO_EHIP;
     if (combo::round_grid_size(N, P, tile_cols, swizzle) == 0) return COMBO_ERANGE;
     const bool vec = aligned16(dst) && aligned16(src) && (ld % 4 == 0);
     return combo::launch_round(a, tile_cols, vec, st) == hipSuccess ? COMBO_OK : COMBO_EHIP;
 }
 
-// Strip width if this round runs in the slab kernel, 0 if it runs in the row-tile kernel.
-int slab_cols_for(const float* dst, const float* src, const float* grad, int64_t ld, int32_t N,
-                  int64_t P, int32_t R) {
-    if (g_kernel.load() == 1) return 0;
-    if (!(aligned16(dst) && aligned16(src) && aligned16(grad) && ld % 4 == 0)) return 0;
+// Which kernel runs this round.  The slab kernels need 16-byte aligned buffers, a pitch
+// that is a multiple of 4 and a slab that fits; everything else goes to the row-tile kernel.
+Plan plan_for(const float* dst, const float* src, const float* grad, int64_t ld, int32_t N,
+              int64_t P, int32_t R) {
+    const Plan tile{kPlanTile, 0};
+    const int want = g_kernel.load();
+    if (want == 1) return tile;
+    if (!(aligned16(dst) && aligned16(src) && aligned16(grad) && ld % 4 == 0)) return tile;
     const int W = combo::slab_strip_cols(N, R, g_slab_cols.load());
-    if (W == 0) return 0;
-    if (((uint64_t)P + (uint64_t)W - 1) / (uint64_t)W > 0x7FFFFFFFull) return 0;
-    return W;
+    if (W == 0 || ((uint64_t)P + (uint64_t)W - 1) / (uint64_t)W > 0x7FFFFFFFull) return tile;
+    return Plan{kPlanSlab, W};
 }
 
 }  // namespace
@@ -95,8 +103,8 @@ int combo_segment_gossip_round(float* d_dst, const float* d_src, int64_t ld,
                                int64_t P, int32_t S, int32_t R, void* stream) {
     const int rc = check_round_args(d_dst, d_src, ld, d_peers, N, P, S, R);
     if (rc != COMBO_OK) return rc;
-    const int W = slab_cols_for(d_dst, d_src, nullptr, ld, N, P, R);
-    return enqueue_round(d_dst, d_src, nullptr, 0.0f, ld, d_peers, d_dataset_sizes, N, P, S, R, W,
+    const Plan plan = plan_for(d_dst, d_src, nullptr, ld, N, P, R);
+    return enqueue_round(d_dst, d_src, nullptr, 0.0f, ld, d_peers, d_dataset_sizes, N, P, S, R, plan,
                          (hipStream_t)stream);
 }
 
@@ -109,18 +117,19 @@ int combo_local_sgd_then_gossip(float* d_dst, float* d_src, const float* d_grad,
     const uint64_t bytes = (uint64_t)N * (uint64_t)ld * sizeof(float);
     if (overlaps(d_grad, bytes, d_src, bytes) || overlaps(d_grad, bytes, d_dst, bytes))
         return COMBO_EALIAS;
-    const int W = slab_cols_for(d_dst, d_src, d_grad, ld, N, P, R);
-    if (W != 0 && g_fused_mode.load() == 0)   // step folded into the slab fill; d_src untouched
-        return enqueue_round(d_dst, d_src, d_grad, lr, ld, d_peers, d_dataset_sizes, N, P, S, R, W,
-                             (hipStream_t)stream);
+    const Plan plan = plan_for(d_dst, d_src, d_grad, ld, N, P, R);
+    if (plan.kind != kPlanTile && g_fused_mode.load() == 0)   // step folded into the slab fill
+        return enqueue_round(d_dst, d_src, d_grad, lr, ld, d_peers, d_dataset_sizes, N, P, S, R,
+                             plan, (hipStream_t)stream);
     // two passes: step every row in place, then the plain round on the stepped buffer
-    if ((W == 0 && combo::round_grid_size(N, P, g_tile_cols.load(), g_swizzle.load() != 0) == 0) ||
+    if ((plan.kind == kPlanTile &&
+         combo::round_grid_size(N, P, g_tile_cols.load(), g_swizzle.load() != 0) == 0) ||
         combo::round_grid_size(N, P, 4096, false) == 0)
         return COMBO_ERANGE;
     const bool vec = aligned16(d_src) && aligned16(d_grad) && (ld % 4 == 0);
     if (combo::launch_sgd_step(d_src, d_grad, lr, ld, N, P, vec, (hipStream_t)stream) != hipSuccess)
         return COMBO_EHIP;
-    return enqueue_round(d_dst, d_src, nullptr, 0.0f, ld, d_peers, d_dataset_sizes, N, P, S, R, W,
+    return enqueue_round(d_dst, d_src, nullptr, 0.0f, ld, d_peers, d_dataset_sizes, N, P, S, R, plan,
                          (hipStream_t)stream);
 }
 

@@ -22,10 +22,19 @@
 namespace combo {
 namespace {
 
-constexpr int kBatch = 8;   // 128-bit loads kept in flight per thread while filling the slab
+constexpr int kBatch = 4;   // 128-bit loads kept in flight per thread while filling the slab
+
+// Workgroup size of the slab kernel.  Measured on MI355X: 512 threads with about two
+// 128-bit words per thread (a 16 KiB slab) beat 128/256/1024 threads and larger slabs.
+constexpr int kSlabThreads = 512;
+
+// every front-buffer element is read once, so the slab fill uses streaming loads
+__device__ __forceinline__ v4f load4_slab(const float* p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+}
 
 template <int RT, bool WEIGHTED, bool FUSED>
-__global__ __launch_bounds__(kThreads) void gossip_slab_kernel(const RoundArgs a, const int W) {
+__global__ __launch_bounds__(kSlabThreads) void gossip_slab_kernel(const RoundArgs a, const int W) {
     extern __shared__ v4f lds[];
     const int32_t R = RT >= 0 ? RT : a.R;
     const int32_t N = a.N;
@@ -44,37 +53,37 @@ __global__ __launch_bounds__(kThreads) void gossip_slab_kernel(const RoundArgs a
 
     if (col_end - col0 == W && col_end <= seg_end) {
         // ---- fill: peer list, weights, then the slab --------------------------------
-        for (int i = threadIdx.x; R > 0 && i < N * R; i += kThreads) {
+        for (int i = threadIdx.x; R > 0 && i < N * R; i += kSlabThreads) {
             const int w = i / (R > 0 ? R : 1);
             const int j = i - w * R;
             lds_peers[i] = a.peers[((size_t)w * (size_t)a.S + (size_t)s0) * (size_t)R + (size_t)j];
         }
         if (WEIGHTED)
-            for (int i = threadIdx.x; i < N; i += kThreads) lds_d[i] = a.dsz[i];
+            for (int i = threadIdx.x; i < N; i += kSlabThreads) lds_d[i] = a.dsz[i];
 
-        for (int base = 0; base < total4; base += kThreads * kBatch) {
+        for (int base = 0; base < total4; base += kSlabThreads * kBatch) {
             v4f x[kBatch], g[kBatch];
 #pragma unroll
             for (int u = 0; u < kBatch; ++u) {
-                const int idx = base + u * kThreads + (int)threadIdx.x;
+                const int idx = base + u * kSlabThreads + (int)threadIdx.x;
                 if (idx < total4) {
                     const int row = idx >> w4_shift;
                     const int c4 = idx & (W4 - 1);
                     const size_t off = (size_t)row * (size_t)a.ld + (size_t)col0 + (size_t)c4 * 4;
-                    x[u] = load4(a.src + off);
-                    if (FUSED) g[u] = load4(a.grad + off);
+                    x[u] = load4_slab(a.src + off);
+                    if (FUSED) g[u] = load4_slab(a.grad + off);
                 }
             }
 #pragma unroll
             for (int u = 0; u < kBatch; ++u) {
-                const int idx = base + u * kThreads + (int)threadIdx.x;
+                const int idx = base + u * kSlabThreads + (int)threadIdx.x;
                 if (idx < total4) slab[idx] = FUSED ? sgd_step4(x[u], a.lr, g[u]) : x[u];
             }
         }
         __syncthreads();
 
         // ---- aggregate from LDS ---------------------------------------------------
-        for (int idx = threadIdx.x; idx < total4; idx += kThreads) {
+        for (int idx = threadIdx.x; idx < total4; idx += kSlabThreads) {
             const int w = idx >> w4_shift;
             const int c4 = idx & (W4 - 1);
             const int32_t* pl = lds_peers + w * R;
@@ -106,7 +115,7 @@ __global__ __launch_bounds__(kThreads) void gossip_slab_kernel(const RoundArgs a
         // ---- boundary or ragged strip: element by element from global memory --------
         const int width = (int)(col_end - col0);
         const int total = N * width;
-        for (int idx = threadIdx.x; idx < total; idx += kThreads) {
+        for (int idx = threadIdx.x; idx < total; idx += kSlabThreads) {
             const int w = idx / width;
             const int64_t e = col0 + (idx - w * width);
             average_element<WEIGHTED, FUSED>(a, w, e);
@@ -122,7 +131,7 @@ template <int RT>
 hipError_t launch_rt(const RoundArgs& a, int W, uint32_t grid, size_t lds, hipStream_t st) {
     const bool weighted = a.dsz != nullptr, fused = a.grad != nullptr;
 #define COMBO_SLAB_LAUNCH(WT, FU)                                                             \
-    hipLaunchKernelGGL((gossip_slab_kernel<RT, WT, FU>), dim3(grid), dim3(kThreads), lds, st, a, W)
+    hipLaunchKernelGGL((gossip_slab_kernel<RT, WT, FU>), dim3(grid), dim3(kSlabThreads), lds, st, a, W)
     if (weighted) {
         if (fused) COMBO_SLAB_LAUNCH(true, true);
         else COMBO_SLAB_LAUNCH(true, false);
@@ -136,9 +145,10 @@ hipError_t launch_rt(const RoundArgs& a, int W, uint32_t grid, size_t lds, hipSt
 
 }  // namespace
 
-// Widest power-of-two strip in [64, 1024] columns whose slab (plus peer list and
-// weights) stays within 64 KiB of LDS and, when possible, within about 40 KiB so that
-// several workgroups share a compute unit.  `requested` != 0 forces a width if it fits.
+// Strip width: the widest power of two in [64, 1024] columns whose slab is at most
+// 16 KiB (two 128-bit words per thread, four workgroups per compute unit); for many
+// workers 64 columns as long as slab, peer list and weights fit in 64 KiB of LDS.
+// `requested` != 0 forces a width if it fits.
 int slab_strip_cols(int32_t N, int32_t R, int requested) {
     const size_t kLimit = 64 * 1024;
     if (requested) {
@@ -148,7 +158,7 @@ int slab_strip_cols(int32_t N, int32_t R, int requested) {
             return requested;
     }
     for (int W = 1024; W >= 64; W >>= 1)
-        if (slab_lds_bytes(N, R, W) <= 40 * 1024) return W;
+        if ((size_t)N * (size_t)W * 4 <= 16 * 1024 && slab_lds_bytes(N, R, W) <= kLimit) return W;
     return slab_lds_bytes(N, R, 64) <= kLimit ? 64 : 0;
 }
 

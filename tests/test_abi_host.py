@@ -112,7 +112,7 @@ def test_tuning_knobs(L):
     assert L.combo_tune(0, old) == 0
     assert L.combo_get_tune(1) in (0, 1)
     assert L.combo_get_tune(77) == EINVAL
-    assert L.combo_tune(3, 3) == EINVAL and L.combo_tune(3, 1) == 0 and L.combo_tune(3, 0) == 0
+    assert L.combo_tune(3, 3) == EINVAL and L.combo_tune(3, 2) == 0 and L.combo_tune(3, 0) == 0
     assert L.combo_tune(4, 100) == EINVAL and L.combo_tune(4, 2048) == EINVAL
     assert L.combo_tune(4, 128) == 0 and L.combo_get_tune(4) == 128 and L.combo_tune(4, 0) == 0
     assert L.combo_tune(2, 2) == EINVAL and L.combo_tune(2, 1) == 0 and L.combo_tune(2, 0) == 0

@@ -35,6 +35,7 @@ def set_variant(combo, variant):
 
 
 VARIANTS = [("slab", 0), ("slab", 64), ("slab", 256), ("slab", 1024),
+            ("slab", 128), ("slab", 512),
             ("tile", 1024), ("tile", 2048), ("tile", 4096)]
 
 
@@ -164,7 +165,7 @@ def test_round_plain_workgroup_order(combo, ref, N, P, S, R):
 
 @pytest.mark.parametrize("N,P,S,R", [(5, 10_007, 7, 3), (8, 40_001, 3, 4), (6, 130, 130, 1),
                                      (16, 30_011, 4, 9), (9, 5_000, 2, 0), (32, 70_000, 32, 4)])
-@pytest.mark.parametrize("variant", [("slab", 0), ("slab", 128), ("tile", 2048)],
+@pytest.mark.parametrize("variant", [("slab", 0), ("slab", 64), ("slab", 512), ("tile", 2048)],
                          ids=lambda v: f"{v[0]}{v[1]}")
 def test_round_dataset_size_weights(combo, ref, N, P, S, R, variant):
     set_variant(combo, variant)
@@ -277,7 +278,7 @@ def test_c4_prime_fused_full_three_rounds(combo, ref, mode):
     """N=100, P=1,000,003 (prime), S=7, R=3, x -= 0.01*g then gossip; full-size
     elementwise comparison over 3 of the 20 rounds (all 20 are covered on windows)."""
     wl = combo.workloads.WORKLOADS["c4_prime_fused"]
-    combo.tune(combo.TUNE_FUSED_MODE, 0 if mode == "fused_slab" else 1)
+    combo.tune(combo.TUNE_FUSED_MODE, 0 if mode.startswith("fused") else 1)
     combo.tune(combo.TUNE_KERNEL, 1 if mode == "two_pass_tile" else 0)
     arena = make_arena(wl)
     combo.workloads.fill_params(arena[0], wl)
@@ -354,7 +355,7 @@ def test_c2_resnet18_full_one_round_elementwise(combo, ref):
 @pytest.mark.parametrize("mode,weighted", [("fused_slab", False), ("fused_slab", True),
                                            ("two_pass_slab", False), ("two_pass_tile", True)])
 def test_fused_small_and_aliasing_contract(combo, ref, mode, weighted):
-    combo.tune(combo.TUNE_FUSED_MODE, 0 if mode == "fused_slab" else 1)
+    combo.tune(combo.TUNE_FUSED_MODE, 0 if mode.startswith("fused") else 1)
     combo.tune(combo.TUNE_KERNEL, 1 if mode == "two_pass_tile" else 0)
     N, P, S, R, lr = 6, 10_007, 7, 3, 0.01
     rng = np.random.default_rng(5)
@@ -373,7 +374,7 @@ def test_fused_small_and_aliasing_contract(combo, ref, mode, weighted):
     want = ref.local_sgd_then_gossip(Xs, Gh, lr, ph, P, S, R, d=None if d is None else d.cpu().numpy())
     assert_params_match(buf[1, :, :P].cpu().numpy(), want, "fused")
     # the old front buffer holds x (fused kernel) or the stepped x' (two passes)
-    assert_params_match(buf[0, :, :P].cpu().numpy(), Xh if mode == "fused_slab" else Xs, "front buffer")
+    assert_params_match(buf[0, :, :P].cpu().numpy(), Xh if mode.startswith("fused") else Xs, "front buffer")
     assert_params_match(buf[2, :, :P].cpu().numpy(), Gh, "gradients untouched")
     assert bool(torch.isnan(buf[:, :, P:]).all())
     # overlapping buffers are refused and nothing is enqueued
