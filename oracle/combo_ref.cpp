@@ -37,6 +37,11 @@
 //                                 row-stochastic matmul, FedAvg limit, identity, ...)
 //   combo_ref_local_sgd_then_gossip  pinned (lr = 0, constant-gradient closed form,
 //                                 matmul of the stepped matrix)
+//   combo_ref_make_peer_table_pooled pinned for structure (all S*R targets distinct
+//                                 when they fit, serve counts differ by at most one,
+//                                 independent queue re-implementation on the same hash
+//                                 words); values: parity unpinned externally, as above
+//   combo_ref_peer_in_degree      pinned (numpy bincount)
 
 #include <cstddef>
 #include <cstdint>
@@ -141,6 +146,72 @@ int combo_ref_make_peer_table(int32_t* peers, int32_t N, int32_t S, int32_t R,
                 peers[((size_t)w * (size_t)S + (size_t)s) * (size_t)R + (size_t)j] = c + (c >= w ? 1 : 0);
             }
         }
+    }
+    return 0;
+}
+
+// ---------------------------------------------------------------------------------
+// Sec. 4.1 step (2) read literally: the targets of ALL S*R requests of a worker are drawn
+// from one pool of the other workers without replacement "until there is no option
+// left", so that requests spread evenly over the workers and, when S*R <= N-1, all
+// segments come from different workers.
+//
+// Reading of what the text leaves open:
+//   * requests are issued segment by segment, replica by replica (s-major, j-minor);
+//   * the pool is a queue holding a uniformly random permutation of the N-1 others
+//     (a full Fisher-Yates shuffle; swap partner of step i of the t-th permutation from
+//     hash(seed ^ POOL_TAG, round, w, t, i)); when the queue is empty the next
+//     permutation becomes the queue ("no option left" -> start over);
+//   * P_l of Eq. (3) is a set, so a request takes the first queue element that this
+//     segment has not already picked (this can only matter right after a refill inside
+//     a segment); skipped elements keep their place at the front of the queue.
+const uint64_t POOL_TAG = 0x706F6F6C65642121ull;
+
+int combo_ref_make_peer_table_pooled(int32_t* peers, int32_t N, int32_t S, int32_t R,
+                                     uint64_t seed, uint64_t round) {
+    if (N < 1 || S < 1 || R < 0 || R > N - 1) return -1;
+    const int32_t M = N - 1;
+    for (int32_t w = 0; w < N; ++w) {
+        std::vector<int32_t> queue;
+        uint64_t epoch = 0;
+        for (int32_t s = 0; s < S; ++s) {
+            int32_t* picks = peers + ((size_t)w * (size_t)S + (size_t)s) * (size_t)R;
+            for (int32_t j = 0; j < R; ++j) {
+                if (queue.empty()) {
+                    for (int32_t v = 0; v < N; ++v)
+                        if (v != w) queue.push_back(v);
+                    for (int32_t i = 0; i + 1 < M; ++i) {
+                        const uint64_t h = peer_hash(seed ^ POOL_TAG, round, (uint64_t)w, epoch, (uint64_t)i);
+                        const int32_t r = i + (int32_t)reduce(h, (uint32_t)(M - i));
+                        const int32_t t = queue[(size_t)i];
+                        queue[(size_t)i] = queue[(size_t)r];
+                        queue[(size_t)r] = t;
+                    }
+                    ++epoch;
+                }
+                size_t pos = 0;
+                for (; pos < queue.size(); ++pos) {
+                    bool taken = false;
+                    for (int32_t k = 0; k < j; ++k) taken = taken || picks[k] == queue[pos];
+                    if (!taken) break;
+                }
+                if (pos == queue.size()) return -2;   // cannot happen while R <= N-1
+                picks[j] = queue[pos];
+                queue.erase(queue.begin() + (std::ptrdiff_t)pos);
+            }
+        }
+    }
+    return 0;
+}
+
+// Serve load of a table: deg[v] = number of (w, s, j) requests whose target is v.
+int combo_ref_peer_in_degree(int32_t* deg, const int32_t* peers, int32_t N, int32_t S, int32_t R) {
+    if (N < 1 || S < 1 || R < 0) return -1;
+    for (int32_t v = 0; v < N; ++v) deg[v] = 0;
+    const size_t n = (size_t)N * (size_t)S * (size_t)R;
+    for (size_t i = 0; i < n; ++i) {
+        if (peers[i] < 0 || peers[i] >= N) return -1;
+        deg[peers[i]] += 1;
     }
     return 0;
 }

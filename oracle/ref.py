@@ -36,6 +36,11 @@ def lib():
         L.combo_ref_make_peer_table.argtypes = [_i32p, ctypes.c_int32, ctypes.c_int32,
                                                 ctypes.c_int32, ctypes.c_uint64, ctypes.c_uint64]
         L.combo_ref_make_peer_table.restype = ctypes.c_int
+        L.combo_ref_make_peer_table_pooled.argtypes = L.combo_ref_make_peer_table.argtypes
+        L.combo_ref_make_peer_table_pooled.restype = ctypes.c_int
+        L.combo_ref_peer_in_degree.argtypes = [_i32p, _i32p, ctypes.c_int32, ctypes.c_int32,
+                                               ctypes.c_int32]
+        L.combo_ref_peer_in_degree.restype = ctypes.c_int
         common = [ctypes.c_int64, _i32p, _f32p, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32,
                   ctypes.c_int32, ctypes.c_int64, ctypes.c_int64]
         L.combo_ref_gossip_round.argtypes = [_f32p, _f32p] + common
@@ -86,6 +91,23 @@ def make_peer_table(N, S, R, seed, rnd):
     if rc:
         raise ValueError("combo_ref_make_peer_table rejected the arguments")
     return peers
+
+
+def make_peer_table_pooled(N, S, R, seed, rnd):
+    peers = np.empty((N, S, R), np.int32)
+    rc = lib().combo_ref_make_peer_table_pooled(_p(peers, _i32p), N, S, R, seed, rnd)
+    if rc:
+        raise ValueError("combo_ref_make_peer_table_pooled rejected the arguments")
+    return peers
+
+
+def peer_in_degree(peers, N, S, R):
+    peers = _peers_arg(peers, N, S, R)
+    deg = np.empty(N, np.int32)
+    rc = lib().combo_ref_peer_in_degree(_p(deg, _i32p), _p(peers, _i32p), N, S, R)
+    if rc:
+        raise ValueError("combo_ref_peer_in_degree rejected the arguments")
+    return deg
 
 
 def _peers_arg(peers, N, S, R):
