@@ -76,6 +76,30 @@ int combo_make_peer_table(int32_t* d_peers, int32_t N, int32_t S, int32_t R,
                           uint64_t seed, uint64_t round, void* stream);
 
 /*
+ * Peer selection as Sec. 4.1 step 2 words it: the targets of ALL S*R requests of a worker
+ * come from one pool of the other workers, drawn without replacement until no option is
+ * left, so requests spread evenly and, when S*R <= N-1, all of a worker's segments come
+ * from different workers.  Requests are issued s-major, j-minor.  The pool is a queue
+ * holding a random permutation of the N-1 others (full Fisher-Yates; swap partner of
+ * step i of the t-th permutation from hash(seed ^ 0x706F6F6C65642121, round, w, t, i),
+ * same hash and reduce as above); an empty queue is replaced by the next permutation; a
+ * request takes the first queue element its segment has not picked yet (Eq. 3's P_l is a
+ * set), skipped elements keeping their place.  Same table layout, arguments and errors
+ * as combo_make_peer_table; the aggregation entry points accept either kind of table.
+ */
+int combo_make_peer_table_pooled(int32_t* d_peers, int32_t N, int32_t S, int32_t R,
+                                 uint64_t seed, uint64_t round, void* stream);
+
+/*
+ * Serve load of a table (the balance Sec. 4.1 step 2 asks for): d_degree[v] = number of
+ * requests (w, s, j) whose target is worker v.  Entries outside [0, N) are not counted.
+ *   d_degree  out, device, int32[N] (overwritten);  d_peers  in, device, int32[N*S*R].
+ * Errors: COMBO_EINVAL for bad sizes or NULL pointers, COMBO_ERANGE for N > 16384.
+ */
+int combo_peer_in_degree(int32_t* d_degree, const int32_t* d_peers, int32_t N, int32_t S,
+                         int32_t R, void* stream);
+
+/*
  * One aggregation round: Eq. (3) on every segment of every worker, written to the back
  * buffer (Eq. 4), all reads from the front buffer.
  *

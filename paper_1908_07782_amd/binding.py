@@ -13,7 +13,7 @@ TUNE_FUSED_MODE = 2
 TUNE_KERNEL = 3
 TUNE_SLAB_COLS = 4
 
-EXPORTS = ("combo_make_peer_table", "combo_segment_gossip_round", "combo_local_sgd_then_gossip",
+EXPORTS = ("combo_make_peer_table", "combo_make_peer_table_pooled", "combo_peer_in_degree", "combo_segment_gossip_round", "combo_local_sgd_then_gossip",
            "combo_tune", "combo_get_tune", "combo_strerror")
 
 _LIB = None
@@ -37,6 +37,10 @@ def lib():
                                   ctypes.c_float)
         L.combo_make_peer_table.argtypes = [vp, i32, i32, i32, u64, u64, vp]
         L.combo_make_peer_table.restype = ctypes.c_int
+        L.combo_make_peer_table_pooled.argtypes = [vp, i32, i32, i32, u64, u64, vp]
+        L.combo_make_peer_table_pooled.restype = ctypes.c_int
+        L.combo_peer_in_degree.argtypes = [vp, vp, i32, i32, i32, vp]
+        L.combo_peer_in_degree.restype = ctypes.c_int
         L.combo_segment_gossip_round.argtypes = [vp, vp, i64, vp, vp, i32, i64, i32, i32, vp]
         L.combo_segment_gossip_round.restype = ctypes.c_int
         L.combo_local_sgd_then_gossip.argtypes = [vp, vp, vp, f32, i64, vp, vp, i32, i64, i32, i32, vp]
@@ -97,6 +101,30 @@ def make_peer_table(peers, N, S, R, seed, rnd, stream=None):
     if rc:
         raise ComboError(rc, "combo_make_peer_table")
     return peers
+
+
+def make_peer_table_pooled(peers, N, S, R, seed, rnd, stream=None):
+    """combo_make_peer_table_pooled: one pool per worker for all of its S*R requests."""
+    if R > 0 and (peers is None or peers.numel() < N * S * R or not peers.is_contiguous()):
+        raise ValueError("peers: need a contiguous int32 device tensor with N*S*R entries")
+    rc = lib().combo_make_peer_table_pooled(_dev_ptr(peers, torch.int32, "peers", optional=(R == 0)),
+                                            N, S, R, ctypes.c_uint64(seed), ctypes.c_uint64(rnd),
+                                            _stream_ptr(stream))
+    if rc:
+        raise ComboError(rc, "combo_make_peer_table_pooled")
+    return peers
+
+
+def peer_in_degree(degree, peers, N, S, R, stream=None):
+    """combo_peer_in_degree: degree (int32[N], device) <- serve load of the table."""
+    if degree.numel() < N or not degree.is_contiguous():
+        raise ValueError("degree: need a contiguous int32 device tensor with N entries")
+    rc = lib().combo_peer_in_degree(_dev_ptr(degree, torch.int32, "degree"),
+                                    _dev_ptr(peers, torch.int32, "peers", optional=(R == 0)),
+                                    N, S, R, _stream_ptr(stream))
+    if rc:
+        raise ComboError(rc, "combo_peer_in_degree")
+    return degree
 
 
 def segment_gossip_round(dst, src, peers, P, S, R, dataset_sizes=None, stream=None):

@@ -98,6 +98,28 @@ int combo_make_peer_table(int32_t* d_peers, int32_t N, int32_t S, int32_t R, uin
     return e == hipSuccess ? COMBO_OK : COMBO_EHIP;
 }
 
+int combo_make_peer_table_pooled(int32_t* d_peers, int32_t N, int32_t S, int32_t R, uint64_t seed,
+                                 uint64_t round, void* stream) {
+    if (N < 1 || S < 1 || R < 0 || R > N - 1) return COMBO_EINVAL;
+    if (R == 0) return COMBO_OK;
+    if (d_peers == nullptr) return COMBO_EINVAL;
+    if (N > 16384) return COMBO_ERANGE;
+    const hipError_t e = combo::launch_peer_table_pooled(d_peers, N, S, R, seed, round,
+                                                         (hipStream_t)stream);
+    return e == hipSuccess ? COMBO_OK : COMBO_EHIP;
+}
+
+int combo_peer_in_degree(int32_t* d_degree, const int32_t* d_peers, int32_t N, int32_t S, int32_t R,
+                         void* stream) {
+    if (N < 1 || S < 1 || R < 0 || d_degree == nullptr) return COMBO_EINVAL;
+    if (R > 0 && d_peers == nullptr) return COMBO_EINVAL;
+    if (N > 16384) return COMBO_ERANGE;
+    const uint64_t entries = (uint64_t)N * (uint64_t)S * (uint64_t)R;
+    const hipError_t e = combo::launch_peer_in_degree(d_degree, d_peers, N, entries,
+                                                      (hipStream_t)stream);
+    return e == hipSuccess ? COMBO_OK : COMBO_EHIP;
+}
+
 int combo_segment_gossip_round(float* d_dst, const float* d_src, int64_t ld,
                                const int32_t* d_peers, const float* d_dataset_sizes, int32_t N,
                                int64_t P, int32_t S, int32_t R, void* stream) {

@@ -36,6 +36,11 @@ hipError_t launch_sgd_step(float* x, const float* g, float lr, int64_t ld, int32
 hipError_t launch_peer_table(int32_t* peers, int32_t N, int32_t S, int32_t R, uint64_t seed,
                              uint64_t round, hipStream_t st);
 
+hipError_t launch_peer_table_pooled(int32_t* peers, int32_t N, int32_t S, int32_t R,
+                                    uint64_t seed, uint64_t round, hipStream_t st);
+hipError_t launch_peer_in_degree(int32_t* deg, const int32_t* peers, int32_t N, uint64_t entries,
+                                 hipStream_t st);
+
 // Slab kernel: one workgroup stages all N rows of a strip of `strip_cols` columns in
 // LDS.  slab_strip_cols() picks the strip width for N workers (0: does not fit in LDS).
 int slab_strip_cols(int32_t N, int32_t R, int requested);

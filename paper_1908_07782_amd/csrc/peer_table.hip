@@ -58,7 +58,92 @@ __global__ __launch_bounds__(64) void peer_table_kernel(int32_t* __restrict__ pe
     }
 }
 
+// Pooled selection (Sec. 4.1 step 2 as written): all S*R requests of a worker draw from
+// one queue holding a random permutation of the other workers; an empty queue is
+// replaced by the next permutation; a request takes the first queue element that its
+// segment has not picked yet, skipped elements keep their place.  The draw is a
+// dependent chain per worker, so one lane of one wavefront walks it with the queue in
+// LDS: queue[head..M) are the elements still in the pool.
+constexpr uint64_t kPoolTag = 0x706F6F6C65642121ull;
+
+__global__ __launch_bounds__(64) void peer_table_pooled_kernel(int32_t* __restrict__ peers,
+                                                               int32_t N, int32_t S, int32_t R,
+                                                               uint64_t seed, uint64_t round) {
+    extern __shared__ int32_t queue[];           // N-1 slots
+    if (threadIdx.x != 0) return;
+    const int32_t M = N - 1;
+    const int32_t w = (int32_t)blockIdx.x;
+    uint64_t hw = finalise((seed ^ kPoolTag) + kGamma);
+    hw = take_in(hw, round);
+    hw = take_in(hw, (uint64_t)w);
+    int32_t head = M;                             // empty pool
+    uint64_t epoch = 0;
+    for (int32_t s = 0; s < S; ++s) {
+        int32_t* picks = peers + ((size_t)w * (size_t)S + (size_t)s) * (size_t)R;
+        for (int32_t j = 0; j < R; ++j) {
+            if (head == M) {
+                // next permutation of the others: full Fisher-Yates
+                for (int32_t i = 0; i < M; ++i) queue[i] = i + (i >= w ? 1 : 0);
+                const uint64_t he = take_in(hw, epoch);
+                for (int32_t i = 0; i + 1 < M; ++i) {
+                    const uint64_t word = take_in(he, (uint64_t)i);
+                    const int32_t r = i + (int32_t)(((word >> 32) * (uint64_t)(uint32_t)(M - i)) >> 32);
+                    const int32_t t = queue[i];
+                    queue[i] = queue[r];
+                    queue[r] = t;
+                }
+                head = 0;
+                ++epoch;
+            }
+            // first pool element this segment has not picked; at most j elements are skipped
+            int32_t pos = head;
+            for (; pos < M; ++pos) {
+                const int32_t c = queue[pos];
+                bool taken = false;
+                for (int32_t k = 0; k < j; ++k) taken = taken || (picks[k] == c);
+                if (!taken) break;
+            }
+            if (pos == M) pos = M - 1;            // unreachable while R <= N-1; keeps indices in range
+            const int32_t c = queue[pos];
+            for (int32_t q = pos; q > head; --q) queue[q] = queue[q - 1];   // skipped keep their order
+            ++head;
+            picks[j] = c;
+        }
+    }
+}
+
+// Serve load: deg[v] = number of requests (w, s, j) whose target is v.  One workgroup,
+// LDS histogram, integer atomics (the result does not depend on their order).
+__global__ __launch_bounds__(1024) void peer_in_degree_kernel(int32_t* __restrict__ deg,
+                                                              const int32_t* __restrict__ peers,
+                                                              int32_t N, uint64_t entries) {
+    extern __shared__ int32_t hist[];
+    for (int32_t i = threadIdx.x; i < N; i += 1024) hist[i] = 0;
+    __syncthreads();
+    for (uint64_t i = threadIdx.x; i < entries; i += 1024) {
+        const int32_t v = peers[i];
+        if (v >= 0 && v < N) atomicAdd(&hist[v], 1);
+    }
+    __syncthreads();
+    for (int32_t i = threadIdx.x; i < N; i += 1024) deg[i] = hist[i];
+}
+
 }  // namespace
+
+hipError_t launch_peer_table_pooled(int32_t* peers, int32_t N, int32_t S, int32_t R, uint64_t seed,
+                                    uint64_t round, hipStream_t st) {
+    const size_t lds = (size_t)(N > 1 ? N - 1 : 1) * sizeof(int32_t);
+    hipLaunchKernelGGL(peer_table_pooled_kernel, dim3((uint32_t)N), dim3(64), lds, st, peers, N, S,
+                       R, seed, round);
+    return hipGetLastError();
+}
+
+hipError_t launch_peer_in_degree(int32_t* deg, const int32_t* peers, int32_t N, uint64_t entries,
+                                 hipStream_t st) {
+    hipLaunchKernelGGL(peer_in_degree_kernel, dim3(1), dim3(1024), (size_t)N * sizeof(int32_t), st,
+                       deg, peers, N, entries);
+    return hipGetLastError();
+}
 
 hipError_t launch_peer_table(int32_t* peers, int32_t N, int32_t S, int32_t R, uint64_t seed,
                              uint64_t round, hipStream_t st) {

@@ -64,6 +64,20 @@ def test_peer_table_argument_errors(L):
     assert f(FAKE_T, 16385, 2, 1, 0, 0, None) == ERANGE      # LDS limit
 
 
+def test_pooled_table_and_degree_argument_errors(L):
+    f = L.combo_make_peer_table_pooled
+    assert f(FAKE_T, 0, 1, 0, 0, 0, None) == EINVAL
+    assert f(FAKE_T, 4, 2, 4, 0, 0, None) == EINVAL
+    assert f(None, 4, 2, 1, 0, 0, None) == EINVAL
+    assert f(None, 4, 2, 0, 0, 0, None) == 0
+    assert f(FAKE_T, 16385, 2, 1, 0, 0, None) == ERANGE
+    g = L.combo_peer_in_degree
+    assert g(None, FAKE_T, 4, 2, 1, None) == EINVAL
+    assert g(FAKE_A, None, 4, 2, 1, None) == EINVAL
+    assert g(FAKE_A, FAKE_T, 0, 2, 1, None) == EINVAL
+    assert g(FAKE_A, FAKE_T, 20000, 2, 1, None) == ERANGE
+
+
 def test_round_argument_errors(L):
     f = L.combo_segment_gossip_round
     ok = dict(N=4, P=1000, S=4, R=2, ld=1024)
