@@ -42,6 +42,11 @@
 //                                 independent queue re-implementation on the same hash
 //                                 words); values: parity unpinned externally, as above
 //   combo_ref_peer_in_degree      pinned (numpy bincount)
+//   combo_ref_make_peer_table_dynamic / combo_ref_gossip_round_dynamic
+//                                 pinned (reduce to the static functions when every
+//                                 worker is active; hand-worked examples with offline
+//                                 workers and newcomers; NaN-poisoned rows that must not
+//                                 be read; dense matmul)
 
 #include <cstddef>
 #include <cstdint>
@@ -293,6 +298,102 @@ int combo_ref_gossip_round_f64(double* Y, const float* X, int64_t ld, const int3
                 for (int32_t j = 0; j < R; ++j)
                     num += (d ? (double)d[pl[j]] : 1.0) * (double)X[(size_t)pl[j] * (size_t)ld + c];
                 Y[(size_t)w * (size_t)ld + c] = num / den;
+            }
+        }
+    }
+    return 0;
+}
+
+// ---------------------------------------------------------------------------------
+// Sec. 4.2 "Dynamic Workers".  status[w]: 0 = offline, 1 = active, 2 = newcomer (joins in
+// this round).
+//
+// Selection: an offline worker sends no request (its entries are -1).  Any other worker
+// draws, per segment, among the ACTIVE others: offline workers have been marked offline
+// and the request re-sent elsewhere, and a newcomer is not yet on anybody's worker list
+// in the round it joins.  With A candidates (listed in increasing worker order) the
+// picks are the first min(R, A) steps of the same hashed Fisher-Yates as in the static
+// table, the span of step j being A - j; unused entries are -1.  With every worker
+// active this is exactly the static table.
+int combo_ref_make_peer_table_dynamic(int32_t* peers, const uint8_t* status, int32_t N, int32_t S,
+                                      int32_t R, uint64_t seed, uint64_t round) {
+    if (N < 1 || S < 1 || R < 0 || R > N - 1) return -1;
+    std::vector<int32_t> cand;
+    for (int32_t w = 0; w < N; ++w) {
+        for (int32_t s = 0; s < S; ++s) {
+            int32_t* out = peers + ((size_t)w * (size_t)S + (size_t)s) * (size_t)R;
+            for (int32_t j = 0; j < R; ++j) out[j] = -1;
+            if (status[w] == 0) continue;
+            cand.clear();
+            for (int32_t v = 0; v < N; ++v)
+                if (v != w && status[v] == 1) cand.push_back(v);
+            const int32_t A = (int32_t)cand.size();
+            const int32_t take = R < A ? R : A;
+            for (int32_t j = 0; j < take; ++j) {
+                const uint64_t h = peer_hash(seed, round, (uint64_t)w, (uint64_t)s, (uint64_t)j);
+                const int32_t r = j + (int32_t)reduce(h, (uint32_t)(A - j));
+                const int32_t t = cand[(size_t)j];
+                cand[(size_t)j] = cand[(size_t)r];
+                cand[(size_t)r] = t;
+                out[j] = cand[(size_t)j];
+            }
+        }
+    }
+    return 0;
+}
+
+// Aggregation with dynamic workers (Sec. 4.2 + Eq. 3):
+//   offline worker:  keeps its parameters, Y[w] = X[w];
+//   active worker:   terms = own value, then the valid (>= 0) table entries in order;
+//   newcomer:        terms = the valid table entries only - it aggregates "without its
+//                    local model"; with no valid entry it keeps what it has.
+//   equal sizes:     acc = first term; acc += each further term; Y = acc * (1.0f/(float)count)
+//   dataset sizes:   num = d*x of the first term, += d*x of the others (product rounded,
+//                    then the sum); den = sum of the terms' d in the same order; Y = num/den
+int combo_ref_gossip_round_dynamic(float* Y, const float* X, int64_t ld, const int32_t* peers,
+                                   const float* d, const uint8_t* status, int32_t N, int64_t P,
+                                   int32_t S, int32_t R, int64_t col0, int64_t ncols) {
+    if (N < 1 || S < 1 || (int64_t)S > P || R < 0 || R > N - 1) return -1;
+    if (col0 < 0 || ncols < 0 || col0 + ncols > P || ld < ncols) return -1;
+    std::vector<int32_t> terms;
+    for (int32_t w = 0; w < N; ++w) {
+        for (int32_t s = 0; s < S; ++s) {
+            const int32_t* pl = peers + ((size_t)w * (size_t)S + (size_t)s) * (size_t)R;
+            int64_t lo = seg_lo(P, S, s), hi = seg_hi(P, S, s);
+            if (lo < col0) lo = col0;
+            if (hi > col0 + ncols) hi = col0 + ncols;
+            terms.clear();
+            if (status[w] == 1) terms.push_back(w);
+            if (status[w] != 0)
+                for (int32_t j = 0; j < R; ++j)
+                    if (pl[j] >= 0) terms.push_back(pl[j]);
+            const size_t n = terms.size();
+            float inv = 0.0f, den = 0.0f;
+            if (n > 0) {
+                inv = 1.0f / (float)n;
+                if (d) {
+                    den = d[terms[0]];
+                    for (size_t k = 1; k < n; ++k) den = den + d[terms[k]];
+                }
+            }
+            for (int64_t e = lo; e < hi; ++e) {
+                const size_t c = (size_t)(e - col0);
+                float out;
+                if (n == 0) {
+                    out = X[(size_t)w * (size_t)ld + c];
+                } else if (!d) {
+                    float acc = X[(size_t)terms[0] * (size_t)ld + c];
+                    for (size_t k = 1; k < n; ++k) acc = acc + X[(size_t)terms[k] * (size_t)ld + c];
+                    out = acc * inv;
+                } else {
+                    float num = d[terms[0]] * X[(size_t)terms[0] * (size_t)ld + c];
+                    for (size_t k = 1; k < n; ++k) {
+                        const float term = d[terms[k]] * X[(size_t)terms[k] * (size_t)ld + c];
+                        num = num + term;
+                    }
+                    out = num / den;
+                }
+                Y[(size_t)w * (size_t)ld + c] = out;
             }
         }
     }

@@ -41,6 +41,15 @@ def lib():
         L.combo_ref_peer_in_degree.argtypes = [_i32p, _i32p, ctypes.c_int32, ctypes.c_int32,
                                                ctypes.c_int32]
         L.combo_ref_peer_in_degree.restype = ctypes.c_int
+        _u8p = ctypes.POINTER(ctypes.c_uint8)
+        L.combo_ref_make_peer_table_dynamic.argtypes = [_i32p, _u8p, ctypes.c_int32, ctypes.c_int32,
+                                                        ctypes.c_int32, ctypes.c_uint64,
+                                                        ctypes.c_uint64]
+        L.combo_ref_make_peer_table_dynamic.restype = ctypes.c_int
+        L.combo_ref_gossip_round_dynamic.argtypes = [_f32p, _f32p, ctypes.c_int64, _i32p, _f32p, _u8p,
+                                                     ctypes.c_int32, ctypes.c_int64, ctypes.c_int32,
+                                                     ctypes.c_int32, ctypes.c_int64, ctypes.c_int64]
+        L.combo_ref_gossip_round_dynamic.restype = ctypes.c_int
         common = [ctypes.c_int64, _i32p, _f32p, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32,
                   ctypes.c_int32, ctypes.c_int64, ctypes.c_int64]
         L.combo_ref_gossip_round.argtypes = [_f32p, _f32p] + common
@@ -108,6 +117,41 @@ def peer_in_degree(peers, N, S, R):
     if rc:
         raise ValueError("combo_ref_peer_in_degree rejected the arguments")
     return deg
+
+
+def _status_arg(status, N):
+    status = np.ascontiguousarray(status, dtype=np.uint8)
+    if status.shape != (N,):
+        raise ValueError("status must have shape (N,)")
+    return status
+
+
+def make_peer_table_dynamic(status, N, S, R, seed, rnd):
+    status = _status_arg(status, N)
+    peers = np.empty((N, S, R), np.int32)
+    rc = lib().combo_ref_make_peer_table_dynamic(_p(peers, _i32p),
+                                                 _p(status, ctypes.POINTER(ctypes.c_uint8)),
+                                                 N, S, R, seed, rnd)
+    if rc:
+        raise ValueError("combo_ref_make_peer_table_dynamic rejected the arguments")
+    return peers
+
+
+def gossip_round_dynamic(X, peers, status, P, S, R, d=None, col0=0):
+    N, ncols = X.shape
+    ld = _check2d(X, np.float32, "X")
+    Y = np.empty_like(X)
+    if _check2d(Y, np.float32, "Y") != ld:
+        raise ValueError("internal: pitch mismatch")
+    peers = _peers_arg(peers, N, S, R)
+    status = _status_arg(status, N)
+    dk, dp = _d_arg(d, N)
+    rc = lib().combo_ref_gossip_round_dynamic(_p(Y, _f32p), _p(X, _f32p), ld, _p(peers, _i32p), dp,
+                                              _p(status, ctypes.POINTER(ctypes.c_uint8)),
+                                              N, P, S, R, col0, ncols)
+    if rc:
+        raise ValueError("combo_ref_gossip_round_dynamic rejected the arguments")
+    return Y
 
 
 def _peers_arg(peers, N, S, R):
