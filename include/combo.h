@@ -125,6 +125,38 @@ int combo_segment_gossip_round(float* d_dst, const float* d_src, int64_t ld,
                                int32_t N, int64_t P, int32_t S, int32_t R, void* stream);
 
 /*
+ * Dynamic workers (Sec. 4.2).  d_status is device uint8[N]: 0 = offline, 1 = active,
+ * 2 = newcomer joining in this round.
+ *
+ * Selection: an offline worker sends no request (all its entries are -1).  Every other
+ * worker draws, per segment, among the ACTIVE others - a worker found offline is marked
+ * offline and the request goes to someone else; a newcomer is not yet on anybody's
+ * worker list.  With A candidates (in increasing worker order) the picks are the first
+ * min(R, A) steps of the hashed Fisher-Yates of combo_make_peer_table, the span of step j
+ * being A - j; unused entries are -1.  With every worker active the table equals
+ * combo_make_peer_table's.  Errors as combo_make_peer_table, plus COMBO_EINVAL for a NULL
+ * d_status.
+ */
+int combo_make_peer_table_dynamic(int32_t* d_peers, const uint8_t* d_status, int32_t N, int32_t S,
+                                  int32_t R, uint64_t seed, uint64_t round, void* stream);
+
+/*
+ * Aggregation with dynamic workers: as combo_segment_gossip_round, except that
+ *   - an offline worker keeps its parameters (dst[w] = src[w]);
+ *   - an active worker averages its own value and the valid (>= 0) entries of its table
+ *     row, in order; a newcomer averages the valid entries only - it aggregates "without
+ *     its local model" - and keeps what it has if there is none;
+ *   - uniform weights scale by 1.0f/(float)(number of terms); with dataset sizes the
+ *     numerator and denominator run over the same terms in the same order.
+ * Rows of offline workers and the own rows of newcomers are never read for anybody else.
+ * Errors as combo_segment_gossip_round, plus COMBO_EINVAL for a NULL d_status.
+ */
+int combo_segment_gossip_round_dynamic(float* d_dst, const float* d_src, int64_t ld,
+                                       const int32_t* d_peers, const float* d_dataset_sizes,
+                                       const uint8_t* d_status, int32_t N, int64_t P, int32_t S,
+                                       int32_t R, void* stream);
+
+/*
  * Local update, then the round (Sec. 4.1 steps 1, 3, 4): first EVERY worker takes one
  * SGD step with the given gradient, x' = x - lr*g (product rounded, then the
  * difference), and only then Eq. (3) is applied to the stepped parameters x' exactly as

@@ -13,7 +13,8 @@ TUNE_FUSED_MODE = 2
 TUNE_KERNEL = 3
 TUNE_SLAB_COLS = 4
 
-EXPORTS = ("combo_make_peer_table", "combo_make_peer_table_pooled", "combo_peer_in_degree", "combo_segment_gossip_round", "combo_local_sgd_then_gossip",
+EXPORTS = ("combo_make_peer_table_dynamic", "combo_segment_gossip_round_dynamic",
+           "combo_make_peer_table", "combo_make_peer_table_pooled", "combo_peer_in_degree", "combo_segment_gossip_round", "combo_local_sgd_then_gossip",
            "combo_tune", "combo_get_tune", "combo_strerror")
 
 _LIB = None
@@ -41,6 +42,10 @@ def lib():
         L.combo_make_peer_table_pooled.restype = ctypes.c_int
         L.combo_peer_in_degree.argtypes = [vp, vp, i32, i32, i32, vp]
         L.combo_peer_in_degree.restype = ctypes.c_int
+        L.combo_make_peer_table_dynamic.argtypes = [vp, vp, i32, i32, i32, u64, u64, vp]
+        L.combo_make_peer_table_dynamic.restype = ctypes.c_int
+        L.combo_segment_gossip_round_dynamic.argtypes = [vp, vp, i64, vp, vp, vp, i32, i64, i32, i32, vp]
+        L.combo_segment_gossip_round_dynamic.restype = ctypes.c_int
         L.combo_segment_gossip_round.argtypes = [vp, vp, i64, vp, vp, i32, i64, i32, i32, vp]
         L.combo_segment_gossip_round.restype = ctypes.c_int
         L.combo_local_sgd_then_gossip.argtypes = [vp, vp, vp, f32, i64, vp, vp, i32, i64, i32, i32, vp]
@@ -125,6 +130,39 @@ def peer_in_degree(degree, peers, N, S, R, stream=None):
     if rc:
         raise ComboError(rc, "combo_peer_in_degree")
     return degree
+
+
+def make_peer_table_dynamic(peers, status, N, S, R, seed, rnd, stream=None):
+    """combo_make_peer_table_dynamic: status is a uint8 device tensor of N entries."""
+    if R > 0 and (peers is None or peers.numel() < N * S * R or not peers.is_contiguous()):
+        raise ValueError("peers: need a contiguous int32 device tensor with N*S*R entries")
+    if status.numel() < N or not status.is_contiguous():
+        raise ValueError("status: need a contiguous uint8 device tensor with N entries")
+    rc = lib().combo_make_peer_table_dynamic(_dev_ptr(peers, torch.int32, "peers", optional=(R == 0)),
+                                             _dev_ptr(status, torch.uint8, "status"), N, S, R,
+                                             ctypes.c_uint64(seed), ctypes.c_uint64(rnd),
+                                             _stream_ptr(stream))
+    if rc:
+        raise ComboError(rc, "combo_make_peer_table_dynamic")
+    return peers
+
+
+def segment_gossip_round_dynamic(dst, src, peers, status, P, S, R, dataset_sizes=None, stream=None):
+    """combo_segment_gossip_round_dynamic on (N, ld)-strided float32 device tensors."""
+    N = src.shape[0]
+    ld = _matrix(src, "src")
+    if _matrix(dst, "dst") != ld or dst.shape[0] != N:
+        raise ValueError("dst must have src's row count and pitch")
+    if status.numel() < N or not status.is_contiguous():
+        raise ValueError("status: need a contiguous uint8 device tensor with N entries")
+    rc = lib().combo_segment_gossip_round_dynamic(
+        _dev_ptr(dst, torch.float32, "dst"), _dev_ptr(src, torch.float32, "src"), ld,
+        _dev_ptr(peers, torch.int32, "peers", optional=(R == 0)),
+        _dev_ptr(dataset_sizes, torch.float32, "dataset_sizes", optional=True),
+        _dev_ptr(status, torch.uint8, "status"), N, P, S, R, _stream_ptr(stream))
+    if rc:
+        raise ComboError(rc, "combo_segment_gossip_round_dynamic")
+    return dst
 
 
 def segment_gossip_round(dst, src, peers, P, S, R, dataset_sizes=None, stream=None):

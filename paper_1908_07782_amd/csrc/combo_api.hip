@@ -43,7 +43,7 @@ int check_round_args(const float* dst, const float* src, int64_t ld, const int32
 // fused_in_round().
 int enqueue_round(float* dst, const float* src, const float* grad, float lr, int64_t ld,
                   const int32_t* peers, const float* dsz, int32_t N, int64_t P, int32_t S,
-                  int32_t R, Plan plan, hipStream_t st) {
+                  int32_t R, Plan plan, hipStream_t st, const uint8_t* status = nullptr) {
     const int tile_cols = g_tile_cols.load();
     const bool swizzle = g_swizzle.load() != 0;
     combo::RoundArgs a;
@@ -52,6 +52,7 @@ int enqueue_round(float* dst, const float* src, const float* grad, float lr, int
     a.peers = peers;
     a.dsz = dsz;
     a.grad = grad;
+    a.status = status;
     a.ld = ld;
     a.P = P;
     a.L = P / S;
@@ -65,6 +66,8 @@ int enqueue_round(float* dst, const float* src, const float* grad, float lr, int
     a.lr = lr;
     if (plan.kind == kPlanSlab)
         return combo::launch_round_slab(a, plan.cols, st) == hipSuccess ? COMBO_OK : COMBO_EHIP;
+    if (status != nullptr)
+        return combo::launch_round_dynamic_elementwise(a, st) == hipSuccess ? COMBO_OK : COMBO_EHIP;
     if (combo::round_grid_size(N, P, tile_cols, swizzle) == 0) return COMBO_ERANGE;
     const bool vec = aligned16(dst) && aligned16(src) && (ld % 4 == 0);
     return combo::launch_round(a, tile_cols, vec, st) == hipSuccess ? COMBO_OK : COMBO_EHIP;
@@ -128,6 +131,31 @@ int combo_segment_gossip_round(float* d_dst, const float* d_src, int64_t ld,
     const Plan plan = plan_for(d_dst, d_src, nullptr, ld, N, P, R);
     return enqueue_round(d_dst, d_src, nullptr, 0.0f, ld, d_peers, d_dataset_sizes, N, P, S, R, plan,
                          (hipStream_t)stream);
+}
+
+int combo_make_peer_table_dynamic(int32_t* d_peers, const uint8_t* d_status, int32_t N, int32_t S,
+                                  int32_t R, uint64_t seed, uint64_t round, void* stream) {
+    if (N < 1 || S < 1 || R < 0 || R > N - 1) return COMBO_EINVAL;
+    if (R == 0) return COMBO_OK;
+    if (d_peers == nullptr || d_status == nullptr) return COMBO_EINVAL;
+    if (N > 16384 || (uint64_t)N * (uint64_t)S > 0x7FFFFFFFull) return COMBO_ERANGE;
+    const hipError_t e = combo::launch_peer_table_dynamic(d_peers, d_status, N, S, R, seed, round,
+                                                          (hipStream_t)stream);
+    return e == hipSuccess ? COMBO_OK : COMBO_EHIP;
+}
+
+int combo_segment_gossip_round_dynamic(float* d_dst, const float* d_src, int64_t ld,
+                                       const int32_t* d_peers, const float* d_dataset_sizes,
+                                       const uint8_t* d_status, int32_t N, int64_t P, int32_t S,
+                                       int32_t R, void* stream) {
+    const int rc = check_round_args(d_dst, d_src, ld, d_peers, N, P, S, R);
+    if (rc != COMBO_OK) return rc;
+    if (d_status == nullptr) return COMBO_EINVAL;
+    const Plan plan = plan_for(d_dst, d_src, nullptr, ld, N, P, R);
+    if (plan.kind == kPlanTile && ((uint64_t)P + 1023) / 1024 * (uint64_t)N > 0x7FFFFFFFull)
+        return COMBO_ERANGE;
+    return enqueue_round(d_dst, d_src, nullptr, 0.0f, ld, d_peers, d_dataset_sizes, N, P, S, R, plan,
+                         (hipStream_t)stream, d_status);
 }
 
 int combo_local_sgd_then_gossip(float* d_dst, float* d_src, const float* d_grad, float lr,

@@ -18,6 +18,7 @@ struct RoundArgs {
     const int32_t* peers;
     const float* dsz;        // dataset sizes |D_j| or nullptr (uniform weights)
     const float* grad;       // gradients for the fused local step, or nullptr
+    const uint8_t* status;   // dynamic workers: 0 offline, 1 active, 2 newcomer; or nullptr
     int64_t ld;              // row pitch in elements
     int64_t P;               // parameters per worker
     int64_t L;               // floor(P / S): length of every segment but the last
@@ -31,6 +32,9 @@ struct RoundArgs {
 
 // launchers (defined in gossip_round.hip / peer_table.hip); return hipGetLastError()
 hipError_t launch_round(const RoundArgs& a, int tile_cols, bool vec, hipStream_t st);
+hipError_t launch_round_dynamic_elementwise(const RoundArgs& a, hipStream_t st);
+hipError_t launch_peer_table_dynamic(int32_t* peers, const uint8_t* status, int32_t N, int32_t S,
+                                     int32_t R, uint64_t seed, uint64_t round, hipStream_t st);
 hipError_t launch_sgd_step(float* x, const float* g, float lr, int64_t ld, int32_t N, int64_t P,
                            bool vec, hipStream_t st);
 hipError_t launch_peer_table(int32_t* peers, int32_t N, int32_t S, int32_t R, uint64_t seed,

@@ -227,6 +227,18 @@ __global__ __launch_bounds__(kThreads) void sgd_step_kernel(float* __restrict__ 
     }
 }
 
+// Dynamic workers (Sec. 4.2) without the LDS slab: one element per lane, any alignment.
+// Only used when the slab kernel cannot run (unaligned buffers or very many workers).
+template <bool WEIGHTED>
+__global__ __launch_bounds__(kThreads) void gossip_dynamic_elementwise_kernel(const RoundArgs a) {
+    const uint32_t w = blockIdx.x / a.tiles_per_row;
+    const uint32_t tile = blockIdx.x - w * a.tiles_per_row;
+    const int64_t col_begin = (int64_t)tile * 1024;
+    const int64_t col_end = col_begin + 1024 < a.P ? col_begin + 1024 : a.P;
+    for (int64_t e = col_begin + threadIdx.x; e < col_end; e += kThreads)
+        average_element_dynamic<WEIGHTED>(a, (int32_t)w, e);
+}
+
 template <int RT, int VPT>
 hipError_t launch_rt_vpt(const RoundArgs& a, bool vec, uint32_t grid, hipStream_t st) {
     const bool weighted = a.dsz != nullptr;
@@ -282,6 +294,21 @@ hipError_t launch_round(const RoundArgs& a, int tile_cols, bool vec, hipStream_t
         case 4096: return launch_vpt<4>(a, vec, grid, st);
         default: return hipErrorInvalidValue;
     }
+}
+
+hipError_t launch_round_dynamic_elementwise(const RoundArgs& a_in, hipStream_t st) {
+    RoundArgs a = a_in;
+    const uint64_t tiles = ((uint64_t)a.P + 1023) / 1024;
+    const uint64_t grid = tiles * (uint64_t)a.N;
+    if (grid > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    a.tiles_per_row = (uint32_t)tiles;
+    if (a.dsz != nullptr)
+        hipLaunchKernelGGL(gossip_dynamic_elementwise_kernel<true>, dim3((uint32_t)grid),
+                           dim3(kThreads), 0, st, a);
+    else
+        hipLaunchKernelGGL(gossip_dynamic_elementwise_kernel<false>, dim3((uint32_t)grid),
+                           dim3(kThreads), 0, st, a);
+    return hipGetLastError();
 }
 
 hipError_t launch_sgd_step(float* x, const float* g, float lr, int64_t ld, int32_t N, int64_t P,

@@ -33,7 +33,9 @@ __device__ __forceinline__ v4f load4_slab(const float* p) {
     return __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
 }
 
-template <int RT, bool WEIGHTED, bool FUSED>
+// DYNAMIC: Sec. 4.2 semantics (offline rows copied, newcomers aggregated without their own
+// value, unused table slots < 0 skipped, scale by the number of terms).
+template <int RT, bool WEIGHTED, bool FUSED, bool DYNAMIC>
 __global__ __launch_bounds__(kSlabThreads) void gossip_slab_kernel(const RoundArgs a, const int W) {
     extern __shared__ v4f lds[];
     const int32_t R = RT >= 0 ? RT : a.R;
@@ -45,6 +47,7 @@ __global__ __launch_bounds__(kSlabThreads) void gossip_slab_kernel(const RoundAr
     v4f* slab = lds;                                                   // [N][W4]
     int32_t* lds_peers = reinterpret_cast<int32_t*>(lds + total4);     // [N][R]
     float* lds_d = reinterpret_cast<float*>(lds_peers + (size_t)N * (size_t)R);   // [N]
+    int32_t* lds_status = reinterpret_cast<int32_t*>(lds_d + N);                  // [N]
 
     const int64_t col0 = (int64_t)blockIdx.x * W;
     const int64_t col_end = col0 + W < a.P ? col0 + W : a.P;
@@ -60,6 +63,8 @@ __global__ __launch_bounds__(kSlabThreads) void gossip_slab_kernel(const RoundAr
         }
         if (WEIGHTED)
             for (int i = threadIdx.x; i < N; i += kSlabThreads) lds_d[i] = a.dsz[i];
+        if (DYNAMIC)
+            for (int i = threadIdx.x; i < N; i += kSlabThreads) lds_status[i] = a.status[i];
 
         for (int base = 0; base < total4; base += kSlabThreads * kBatch) {
             v4f x[kBatch], g[kBatch];
@@ -89,7 +94,32 @@ __global__ __launch_bounds__(kSlabThreads) void gossip_slab_kernel(const RoundAr
             const int32_t* pl = lds_peers + w * R;
             v4f acc = slab[idx];
             v4f y;
-            if (!WEIGHTED) {
+            if (DYNAMIC) {
+                const v4f own = acc;
+                const int st = lds_status[w];
+                int cnt = 0;
+                float den = 0.0f;
+                if (st == 1) {
+                    if (WEIGHTED) { den = lds_d[w]; acc = scale4(den, own); }
+                    cnt = 1;
+                }
+                if (st != 0) {
+                    for (int j = 0; j < R; ++j) {
+                        const int p = pl[j];
+                        if (p < 0) continue;
+                        v4f v = slab[(p << w4_shift) + c4];
+                        if (WEIGHTED) {
+                            const float dp = lds_d[p];
+                            v = scale4(dp, v);
+                            den = cnt == 0 ? dp : __fadd_rn(den, dp);
+                        }
+                        acc = cnt == 0 ? v : add4(acc, v);
+                        ++cnt;
+                    }
+                }
+                if (cnt == 0) y = own;
+                else y = WEIGHTED ? div4(acc, den) : scale4(__fdiv_rn(1.0f, (float)cnt), acc);
+            } else if (!WEIGHTED) {
                 if (RT >= 0) {
 #pragma unroll
                     for (int j = 0; j < (RT >= 0 ? RT : 0); ++j)
@@ -118,20 +148,23 @@ __global__ __launch_bounds__(kSlabThreads) void gossip_slab_kernel(const RoundAr
         for (int idx = threadIdx.x; idx < total; idx += kSlabThreads) {
             const int w = idx / width;
             const int64_t e = col0 + (idx - w * width);
-            average_element<WEIGHTED, FUSED>(a, w, e);
+            if (DYNAMIC) average_element_dynamic<WEIGHTED>(a, w, e);
+            else average_element<WEIGHTED, FUSED>(a, w, e);
         }
     }
 }
 
 size_t slab_lds_bytes(int32_t N, int32_t R, int W) {
-    return (size_t)N * (size_t)W * 4 + (size_t)N * (size_t)R * 4 + (size_t)N * 4;
+    // slab, peer list, dataset sizes, status
+    return (size_t)N * (size_t)W * 4 + (size_t)N * (size_t)R * 4 + (size_t)N * 4 + (size_t)N * 4;
 }
 
 template <int RT>
 hipError_t launch_rt(const RoundArgs& a, int W, uint32_t grid, size_t lds, hipStream_t st) {
     const bool weighted = a.dsz != nullptr, fused = a.grad != nullptr;
 #define COMBO_SLAB_LAUNCH(WT, FU)                                                             \
-    hipLaunchKernelGGL((gossip_slab_kernel<RT, WT, FU>), dim3(grid), dim3(kSlabThreads), lds, st, a, W)
+    hipLaunchKernelGGL((gossip_slab_kernel<RT, WT, FU, false>), dim3(grid), dim3(kSlabThreads), lds, \
+                       st, a, W)
     if (weighted) {
         if (fused) COMBO_SLAB_LAUNCH(true, true);
         else COMBO_SLAB_LAUNCH(true, false);
@@ -167,6 +200,16 @@ hipError_t launch_round_slab(const RoundArgs& a, int W, hipStream_t st) {
     if (strips > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const size_t lds = slab_lds_bytes(a.N, a.R, W);
     const uint32_t grid = (uint32_t)strips;
+    if (a.status != nullptr) {
+        // dynamic workers: run-time replica loop, no fused step
+        if (a.dsz != nullptr)
+            hipLaunchKernelGGL((gossip_slab_kernel<-1, true, false, true>), dim3(grid),
+                               dim3(kSlabThreads), lds, st, a, W);
+        else
+            hipLaunchKernelGGL((gossip_slab_kernel<-1, false, false, true>), dim3(grid),
+                               dim3(kSlabThreads), lds, st, a, W);
+        return hipGetLastError();
+    }
     switch (a.R) {
         case 0: return launch_rt<0>(a, W, grid, lds, st);
         case 1: return launch_rt<1>(a, W, grid, lds, st);

@@ -112,6 +112,52 @@ __global__ __launch_bounds__(64) void peer_table_pooled_kernel(int32_t* __restri
     }
 }
 
+// Selection with dynamic workers (Sec. 4.2): candidates are the ACTIVE others (offline
+// workers are not asked, newcomers are not yet known to anyone); an offline requester
+// asks nobody.  One wavefront per (w, s): the lanes compact the candidate list into LDS
+// with ballots (increasing worker order), lane 0 performs min(R, #candidates) swap steps
+// of the same hashed Fisher-Yates; unused slots are -1.
+__global__ __launch_bounds__(64) void peer_table_dynamic_kernel(int32_t* __restrict__ peers,
+                                                                const uint8_t* __restrict__ status,
+                                                                int32_t N, int32_t S, int32_t R,
+                                                                uint64_t seed, uint64_t round) {
+    extern __shared__ int32_t cand[];            // up to N-1 candidates
+    const uint32_t pair = blockIdx.x;
+    const int32_t w = (int32_t)(pair / (uint32_t)S);
+    const int32_t s = (int32_t)(pair - (uint32_t)w * (uint32_t)S);
+    const int lane = (int)threadIdx.x;
+    int32_t* out = peers + (size_t)pair * (size_t)R;
+
+    int32_t count = 0;
+    if (status[w] != 0) {
+        for (int32_t base = 0; base < N; base += 64) {
+            const int32_t v = base + lane;
+            const bool ok = v < N && v != w && status[v] == 1;
+            const uint64_t mask = __ballot(ok);
+            if (ok) cand[count + __popcll(mask & ((1ull << lane) - 1ull))] = v;
+            count += (int32_t)__popcll(mask);
+        }
+    }
+    __syncthreads();
+
+    if (lane == 0) {
+        uint64_t h = finalise(seed + kGamma);
+        h = take_in(h, round);
+        h = take_in(h, (uint64_t)w);
+        h = take_in(h, (uint64_t)s);
+        const int32_t take = R < count ? R : count;
+        for (int32_t j = 0; j < take; ++j) {
+            const uint64_t word = take_in(h, (uint64_t)j);
+            const int32_t r = j + (int32_t)(((word >> 32) * (uint64_t)(uint32_t)(count - j)) >> 32);
+            const int32_t picked = cand[r];
+            cand[r] = cand[j];
+            cand[j] = picked;
+            out[j] = picked;
+        }
+        for (int32_t j = take; j < R; ++j) out[j] = -1;
+    }
+}
+
 // Serve load: deg[v] = number of requests (w, s, j) whose target is v.  One workgroup,
 // LDS histogram, integer atomics (the result does not depend on their order).
 __global__ __launch_bounds__(1024) void peer_in_degree_kernel(int32_t* __restrict__ deg,
@@ -135,6 +181,15 @@ hipError_t launch_peer_table_pooled(int32_t* peers, int32_t N, int32_t S, int32_
     const size_t lds = (size_t)(N > 1 ? N - 1 : 1) * sizeof(int32_t);
     hipLaunchKernelGGL(peer_table_pooled_kernel, dim3((uint32_t)N), dim3(64), lds, st, peers, N, S,
                        R, seed, round);
+    return hipGetLastError();
+}
+
+hipError_t launch_peer_table_dynamic(int32_t* peers, const uint8_t* status, int32_t N, int32_t S,
+                                     int32_t R, uint64_t seed, uint64_t round, hipStream_t st) {
+    const uint32_t blocks = (uint32_t)N * (uint32_t)S;
+    const size_t lds = (size_t)(N > 1 ? N - 1 : 1) * sizeof(int32_t);
+    hipLaunchKernelGGL(peer_table_dynamic_kernel, dim3(blocks), dim3(64), lds, st, peers, status, N,
+                       S, R, seed, round);
     return hipGetLastError();
 }
 

@@ -98,5 +98,42 @@ __device__ __forceinline__ void average_element(const RoundArgs& a, int32_t w, i
     a.dst[(size_t)w * (size_t)a.ld + (size_t)e] = out;
 }
 
+// Eq. (3) with dynamic workers (Sec. 4.2) for one element.  status: 0 offline (keeps its
+// value), 1 active (own value, then the valid table entries), 2 newcomer (valid table
+// entries only; none -> keeps its value).  Table entries < 0 are unused slots.
+template <bool WEIGHTED>
+__device__ __forceinline__ void average_element_dynamic(const RoundArgs& a, int32_t w, int64_t e) {
+    const int32_t s = segment_of(e, a);
+    const int32_t* pl = a.peers + ((size_t)w * (size_t)a.S + (size_t)s) * (size_t)a.R;
+    const float own = a.src[(size_t)w * (size_t)a.ld + (size_t)e];
+    const int st = a.status[w];
+    int cnt = 0;
+    float acc = 0.0f, den = 0.0f;
+    if (st == 1) {
+        if (WEIGHTED) { den = a.dsz[w]; acc = __fmul_rn(den, own); }
+        else acc = own;
+        cnt = 1;
+    }
+    if (st != 0) {
+        for (int32_t j = 0; j < a.R; ++j) {
+            const int32_t p = pl[j];
+            if (p < 0) continue;
+            const float v = a.src[(size_t)p * (size_t)a.ld + (size_t)e];
+            if (WEIGHTED) {
+                const float dp = a.dsz[p];
+                const float t = __fmul_rn(dp, v);
+                acc = cnt == 0 ? t : __fadd_rn(acc, t);
+                den = cnt == 0 ? dp : __fadd_rn(den, dp);
+            } else {
+                acc = cnt == 0 ? v : __fadd_rn(acc, v);
+            }
+            ++cnt;
+        }
+    }
+    float out = own;
+    if (cnt > 0) out = WEIGHTED ? __fdiv_rn(acc, den) : __fmul_rn(acc, __fdiv_rn(1.0f, (float)cnt));
+    a.dst[(size_t)w * (size_t)a.ld + (size_t)e] = out;
+}
+
 }  // namespace combo
 #endif

@@ -78,6 +78,19 @@ def test_pooled_table_and_degree_argument_errors(L):
     assert g(FAKE_A, FAKE_T, 20000, 2, 1, None) == ERANGE
 
 
+def test_dynamic_argument_errors(L):
+    f = L.combo_make_peer_table_dynamic
+    assert f(FAKE_T, None, 4, 2, 1, 0, 0, None) == EINVAL
+    assert f(None, FAKE_C, 4, 2, 1, 0, 0, None) == EINVAL
+    assert f(FAKE_T, FAKE_C, 4, 2, 4, 0, 0, None) == EINVAL
+    assert f(FAKE_T, FAKE_C, 16385, 2, 1, 0, 0, None) == ERANGE
+    assert f(None, None, 4, 2, 0, 0, 0, None) == 0
+    g = L.combo_segment_gossip_round_dynamic
+    assert g(FAKE_A, FAKE_B, 1024, FAKE_T, None, None, 4, 1000, 4, 2, None) == EINVAL
+    assert g(FAKE_A, FAKE_A, 1024, FAKE_T, None, FAKE_C, 4, 1000, 4, 2, None) == EALIAS
+    assert g(FAKE_A, FAKE_B, 999, FAKE_T, None, FAKE_C, 4, 1000, 4, 2, None) == EINVAL
+
+
 def test_round_argument_errors(L):
     f = L.combo_segment_gossip_round
     ok = dict(N=4, P=1000, S=4, R=2, ld=1024)
