@@ -42,6 +42,8 @@
 //                                 independent queue re-implementation on the same hash
 //                                 words); values: parity unpinned externally, as above
 //   combo_ref_peer_in_degree      pinned (numpy bincount)
+//   combo_ref_aggregation_divergence  pinned (numpy float64 mean / squared norms,
+//                                 closed forms: identical workers, +x/-x pair)
 //   combo_ref_make_peer_table_dynamic / combo_ref_gossip_round_dynamic
 //                                 pinned (reduce to the static functions when every
 //                                 worker is active; hand-worked examples with offline
@@ -397,6 +399,33 @@ int combo_ref_gossip_round_dynamic(float* Y, const float* X, int64_t ld, const i
             }
         }
     }
+    return 0;
+}
+
+// ---------------------------------------------------------------------------------
+// Sec. 4.3, Definition 2 (aggregation divergence): the distance between a worker's model
+// W_{t,i} and W_t, the aggregate of ALL workers (the FedAvg output: the dataset-size
+// weighted mean, plain mean for equal sizes).  dist2[i] = sum_e (X[i][e] - mean[e])^2;
+// rho of the definition is bounded below by max_i sqrt(dist2[i]).
+// Accumulated in extended precision so that the result is the exact value to far below
+// the comparison tolerance; the mean is formed in worker order.
+int combo_ref_aggregation_divergence(double* dist2, const float* X, int64_t ld, const float* d,
+                                     int32_t N, int64_t P) {
+    if (N < 1 || P < 1 || ld < P) return -1;
+    std::vector<long double> acc((size_t)N, 0.0L);
+    long double den = 0.0L;
+    for (int32_t w = 0; w < N; ++w) den += d ? (long double)d[w] : 1.0L;
+    for (int64_t e = 0; e < P; ++e) {
+        long double num = 0.0L;
+        for (int32_t w = 0; w < N; ++w)
+            num += (d ? (long double)d[w] : 1.0L) * (long double)X[(size_t)w * (size_t)ld + (size_t)e];
+        const long double mean = num / den;
+        for (int32_t w = 0; w < N; ++w) {
+            const long double diff = (long double)X[(size_t)w * (size_t)ld + (size_t)e] - mean;
+            acc[(size_t)w] += diff * diff;
+        }
+    }
+    for (int32_t w = 0; w < N; ++w) dist2[w] = (double)acc[(size_t)w];
     return 0;
 }
 

@@ -50,6 +50,9 @@ def lib():
                                                      ctypes.c_int32, ctypes.c_int64, ctypes.c_int32,
                                                      ctypes.c_int32, ctypes.c_int64, ctypes.c_int64]
         L.combo_ref_gossip_round_dynamic.restype = ctypes.c_int
+        L.combo_ref_aggregation_divergence.argtypes = [_f64p, _f32p, ctypes.c_int64, _f32p,
+                                                       ctypes.c_int32, ctypes.c_int64]
+        L.combo_ref_aggregation_divergence.restype = ctypes.c_int
         common = [ctypes.c_int64, _i32p, _f32p, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32,
                   ctypes.c_int32, ctypes.c_int64, ctypes.c_int64]
         L.combo_ref_gossip_round.argtypes = [_f32p, _f32p] + common
@@ -117,6 +120,18 @@ def peer_in_degree(peers, N, S, R):
     if rc:
         raise ValueError("combo_ref_peer_in_degree rejected the arguments")
     return deg
+
+
+def aggregation_divergence(X, d=None):
+    """Squared L2 distance of every worker's row from the (weighted) mean of all rows."""
+    N, P = X.shape
+    ld = _check2d(X, np.float32, "X")
+    dist2 = np.empty(N, np.float64)
+    dk, dp = _d_arg(d, N)
+    rc = lib().combo_ref_aggregation_divergence(_p(dist2, _f64p), _p(X, _f32p), ld, dp, N, P)
+    if rc:
+        raise ValueError("combo_ref_aggregation_divergence rejected the arguments")
+    return dist2
 
 
 def _status_arg(status, N):
