@@ -176,6 +176,28 @@ int combo_local_sgd_then_gossip(float* d_dst, float* d_src, const float* d_grad,
                                 int32_t R, void* stream);
 
 /*
+ * Aggregation divergence (Sec. 4.3, Definition 2): how far each worker's model is from the
+ * aggregate of ALL workers (the FedAvg output).
+ *     mean[e]     = sum_w d[w]*x[w][e] / sum_w d[w]      (d = 1 when d_dataset_sizes is NULL)
+ *     d_dist2[w]  = sum_e (x[w][e] - mean[e])^2
+ * evaluated in binary64 (column means in worker order; squared differences summed by a
+ * fixed tree, so repeated calls give identical bits).  The rho of Definition 2 is bounded
+ * below by max_w sqrt(d_dist2[w]).
+ *   d_dist2      out, device, float64[N]
+ *   d_x          in,  device, float32[N][ld]
+ *   d_workspace  scratch, device, 8-byte aligned, at least
+ *                combo_aggregation_divergence_workspace(N, P) bytes; contents irrelevant
+ *                before and after the call
+ * Errors: COMBO_EINVAL for bad sizes, NULL pointers, a workspace that is too small or
+ * misaligned; COMBO_ERANGE when N rows of a 64-column strip do not fit in LDS (N > ~250).
+ * combo_aggregation_divergence_workspace returns the byte count, or a negative status.
+ */
+int64_t combo_aggregation_divergence_workspace(int32_t N, int64_t P);
+int combo_aggregation_divergence(double* d_dist2, const float* d_x, int64_t ld,
+                                 const float* d_dataset_sizes, int32_t N, int64_t P,
+                                 void* d_workspace, int64_t workspace_bytes, void* stream);
+
+/*
  * Performance knobs (process-global, host side only; results never depend on them).
  *   COMBO_TUNE_KERNEL      0: automatic (LDS-slab kernel when the buffers are 16-byte
  *                          aligned, ld % 4 == 0 and N rows of a 64-column strip fit in

@@ -13,7 +13,8 @@ TUNE_FUSED_MODE = 2
 TUNE_KERNEL = 3
 TUNE_SLAB_COLS = 4
 
-EXPORTS = ("combo_make_peer_table_dynamic", "combo_segment_gossip_round_dynamic",
+EXPORTS = ("combo_aggregation_divergence", "combo_aggregation_divergence_workspace",
+           "combo_make_peer_table_dynamic", "combo_segment_gossip_round_dynamic",
            "combo_make_peer_table", "combo_make_peer_table_pooled", "combo_peer_in_degree", "combo_segment_gossip_round", "combo_local_sgd_then_gossip",
            "combo_tune", "combo_get_tune", "combo_strerror")
 
@@ -46,6 +47,10 @@ def lib():
         L.combo_make_peer_table_dynamic.restype = ctypes.c_int
         L.combo_segment_gossip_round_dynamic.argtypes = [vp, vp, i64, vp, vp, vp, i32, i64, i32, i32, vp]
         L.combo_segment_gossip_round_dynamic.restype = ctypes.c_int
+        L.combo_aggregation_divergence_workspace.argtypes = [i32, i64]
+        L.combo_aggregation_divergence_workspace.restype = ctypes.c_int64
+        L.combo_aggregation_divergence.argtypes = [vp, vp, i64, vp, i32, i64, vp, i64, vp]
+        L.combo_aggregation_divergence.restype = ctypes.c_int
         L.combo_segment_gossip_round.argtypes = [vp, vp, i64, vp, vp, i32, i64, i32, i32, vp]
         L.combo_segment_gossip_round.restype = ctypes.c_int
         L.combo_local_sgd_then_gossip.argtypes = [vp, vp, vp, f32, i64, vp, vp, i32, i64, i32, i32, vp]
@@ -163,6 +168,33 @@ def segment_gossip_round_dynamic(dst, src, peers, status, P, S, R, dataset_sizes
     if rc:
         raise ComboError(rc, "combo_segment_gossip_round_dynamic")
     return dst
+
+
+def aggregation_divergence_workspace(N, P):
+    n = lib().combo_aggregation_divergence_workspace(N, P)
+    if n < 0:
+        raise ComboError(int(n), "combo_aggregation_divergence_workspace")
+    return int(n)
+
+
+def aggregation_divergence(dist2, x, P, workspace, dataset_sizes=None, stream=None):
+    """combo_aggregation_divergence: dist2 (float64[N], device) <- squared distance of
+    every row of x[:, :P] from the (weighted) mean row.  workspace: any device tensor of
+    at least aggregation_divergence_workspace(N, P) bytes."""
+    N = x.shape[0]
+    ld = _matrix(x, "x")
+    if dist2.numel() < N or not dist2.is_contiguous():
+        raise ValueError("dist2: need a contiguous float64 device tensor with N entries")
+    if not (workspace.is_cuda and workspace.is_contiguous()):
+        raise ValueError("workspace: need a contiguous device tensor")
+    rc = lib().combo_aggregation_divergence(
+        _dev_ptr(dist2, torch.float64, "dist2"), _dev_ptr(x, torch.float32, "x"), ld,
+        _dev_ptr(dataset_sizes, torch.float32, "dataset_sizes", optional=True), N, P,
+        ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
+        _stream_ptr(stream))
+    if rc:
+        raise ComboError(rc, "combo_aggregation_divergence")
+    return dist2
 
 
 def segment_gossip_round(dst, src, peers, P, S, R, dataset_sizes=None, stream=None):

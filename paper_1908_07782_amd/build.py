@@ -9,7 +9,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcombo.so")
-SOURCES = ["combo_api.hip", "gossip_round.hip", "gossip_slab.hip", "peer_table.hip"]
+SOURCES = ["combo_api.hip", "gossip_round.hip", "gossip_slab.hip", "peer_table.hip",
+           "divergence.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

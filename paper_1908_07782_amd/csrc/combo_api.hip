@@ -183,6 +183,28 @@ int combo_local_sgd_then_gossip(float* d_dst, float* d_src, const float* d_grad,
                          (hipStream_t)stream);
 }
 
+int64_t combo_aggregation_divergence_workspace(int32_t N, int64_t P) {
+    if (N < 1 || P < 1) return COMBO_EINVAL;
+    const int W = combo::divergence_strip_cols(N);
+    if (W == 0) return COMBO_ERANGE;
+    return (int64_t)combo::divergence_grid(P, W) * (int64_t)N * (int64_t)sizeof(double);
+}
+
+int combo_aggregation_divergence(double* d_dist2, const float* d_x, int64_t ld,
+                                 const float* d_dataset_sizes, int32_t N, int64_t P,
+                                 void* d_workspace, int64_t workspace_bytes, void* stream) {
+    if (N < 1 || P < 1 || ld < P || d_dist2 == nullptr || d_x == nullptr) return COMBO_EINVAL;
+    const int64_t need = combo_aggregation_divergence_workspace(N, P);
+    if (need < 0) return (int)need;
+    if (d_workspace == nullptr || workspace_bytes < need || ((uintptr_t)d_workspace & 7u) != 0)
+        return COMBO_EINVAL;
+    const int W = combo::divergence_strip_cols(N);
+    const bool vec = aligned16(d_x) && (ld % 4 == 0);
+    const hipError_t e = combo::launch_divergence(d_dist2, (double*)d_workspace, d_x, ld,
+                                                  d_dataset_sizes, N, P, W, vec, (hipStream_t)stream);
+    return e == hipSuccess ? COMBO_OK : COMBO_EHIP;
+}
+
 int combo_tune(int key, int value) {
     switch (key) {
         case COMBO_TUNE_TILE_COLS:

@@ -45,6 +45,13 @@ hipError_t launch_peer_table_pooled(int32_t* peers, int32_t N, int32_t S, int32_
 hipError_t launch_peer_in_degree(int32_t* deg, const int32_t* peers, int32_t N, uint64_t entries,
                                  hipStream_t st);
 
+// Aggregation divergence (divergence.hip)
+int divergence_strip_cols(int32_t N);
+uint32_t divergence_grid(int64_t P, int strip_cols);
+hipError_t launch_divergence(double* dist2, double* workspace, const float* x, int64_t ld,
+                             const float* dsz, int32_t N, int64_t P, int strip_cols, bool vec,
+                             hipStream_t st);
+
 // Slab kernel: one workgroup stages all N rows of a strip of `strip_cols` columns in
 // LDS.  slab_strip_cols() picks the strip width for N workers (0: does not fit in LDS).
 int slab_strip_cols(int32_t N, int32_t R, int requested);

@@ -91,6 +91,20 @@ def test_dynamic_argument_errors(L):
     assert g(FAKE_A, FAKE_B, 999, FAKE_T, None, FAKE_C, 4, 1000, 4, 2, None) == EINVAL
 
 
+def test_divergence_argument_errors(L):
+    ws = L.combo_aggregation_divergence_workspace
+    assert ws(0, 10) == EINVAL and ws(4, 0) == EINVAL and ws(600, 1000) == ERANGE
+    need = ws(32, 11_689_512)
+    assert need == 2048 * 32 * 8
+    assert ws(4, 100) == 1 * 4 * 8                       # N=4: one 512-column strip
+    f = L.combo_aggregation_divergence
+    assert f(None, FAKE_B, 1024, None, 4, 1000, FAKE_C, 10**6, None) == EINVAL
+    assert f(FAKE_A, FAKE_B, 999, None, 4, 1000, FAKE_C, 10**6, None) == EINVAL
+    assert f(FAKE_A, FAKE_B, 1024, None, 4, 1000, None, 10**6, None) == EINVAL
+    assert f(FAKE_A, FAKE_B, 1024, None, 4, 1000, FAKE_C, 8, None) == EINVAL
+    assert f(FAKE_A, FAKE_B, 1024, None, 4, 1000, ctypes.c_void_p(0x30000004), 10**6, None) == EINVAL
+
+
 def test_round_argument_errors(L):
     f = L.combo_segment_gossip_round
     ok = dict(N=4, P=1000, S=4, R=2, ld=1024)
