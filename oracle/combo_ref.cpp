@@ -37,6 +37,8 @@
 //                                 row-stochastic matmul, FedAvg limit, identity, ...)
 //   combo_ref_local_sgd_then_gossip  pinned (lr = 0, constant-gradient closed form,
 //                                 matmul of the stepped matrix)
+//   combo_ref_local_sgd_steps_then_gossip  pinned (tau = 1 is the single step; tau
+//                                 numpy binary32 multiply/subtract passes then the round)
 //   combo_ref_make_peer_table_pooled pinned for structure (all S*R targets distinct
 //                                 when they fit, serve counts differ by at most one,
 //                                 independent queue re-implementation on the same hash
@@ -444,6 +446,31 @@ int combo_ref_local_sgd_then_gossip(float* Y, float* X, const float* G, float lr
             const size_t k = (size_t)w * (size_t)ld + (size_t)c;
             const float step = lr * G[k];
             X[k] = X[k] - step;
+        }
+    }
+    return combo_ref_gossip_round(Y, X, ld, peers, d, N, P, S, R, col0, ncols);
+}
+
+// Sec. 4.1 step (1) with a communication interval tau > 1: tau SGD steps with given
+// gradients G[k] (k = 0..tau-1, each [N][ld], slice k starting at G + k*N*ld) are applied
+// one after the other, x <- x - lr*G[k] (product rounded, then the difference), on every
+// worker and column of the window; then the round on the stepped X.  X is overwritten
+// by the stepped values.
+int combo_ref_local_sgd_steps_then_gossip(float* Y, float* X, const float* G, int32_t tau, float lr,
+                                          int64_t ld, const int32_t* peers, const float* d,
+                                          int32_t N, int64_t P, int32_t S, int32_t R, int64_t col0,
+                                          int64_t ncols) {
+    if (tau < 0) return -1;
+    if (N < 1 || S < 1 || (int64_t)S > P || R < 0 || R > N - 1) return -1;
+    if (col0 < 0 || ncols < 0 || col0 + ncols > P || ld < ncols) return -1;
+    for (int32_t k = 0; k < tau; ++k) {
+        const float* Gk = G + (size_t)k * (size_t)N * (size_t)ld;
+        for (int32_t w = 0; w < N; ++w) {
+            for (int64_t c = 0; c < ncols; ++c) {
+                const size_t i = (size_t)w * (size_t)ld + (size_t)c;
+                const float step = lr * Gk[i];
+                X[i] = X[i] - step;
+            }
         }
     }
     return combo_ref_gossip_round(Y, X, ld, peers, d, N, P, S, R, col0, ncols);

@@ -61,6 +61,9 @@ def lib():
         L.combo_ref_gossip_round_f64.restype = ctypes.c_int
         L.combo_ref_local_sgd_then_gossip.argtypes = [_f32p, _f32p, _f32p, ctypes.c_float] + common
         L.combo_ref_local_sgd_then_gossip.restype = ctypes.c_int
+        L.combo_ref_local_sgd_steps_then_gossip.argtypes = [_f32p, _f32p, _f32p, ctypes.c_int32,
+                                                            ctypes.c_float] + common
+        L.combo_ref_local_sgd_steps_then_gossip.restype = ctypes.c_int
         _LIB = L
     return _LIB
 
@@ -232,4 +235,23 @@ def local_sgd_then_gossip(X, G, lr, peers, P, S, R, d=None, col0=0):
                                                N, P, S, R, col0, ncols)
     if rc:
         raise ValueError("combo_ref_local_sgd_then_gossip rejected the arguments")
+    return Y
+
+
+def local_sgd_steps_then_gossip(X, G, lr, peers, P, S, R, d=None, col0=0):
+    """G: (tau, N, ncols) float32, C-contiguous with X's pitch.  Steps X in place tau
+    times, then returns the round on the stepped X."""
+    N, ncols = X.shape
+    ld = _check2d(X, np.float32, "X")
+    if not (G.dtype == np.float32 and G.ndim == 3 and G.shape[1:] == X.shape
+            and G.strides == (N * ld * 4, ld * 4, 4)):
+        raise ValueError("G must be (tau, N, ncols) float32 with X's pitch and slice stride N*ld")
+    Y = np.empty_like(X)
+    peers = _peers_arg(peers, N, S, R)
+    dk, dp = _d_arg(d, N)
+    rc = lib().combo_ref_local_sgd_steps_then_gossip(_p(Y, _f32p), _p(X, _f32p), _p(G, _f32p),
+                                                     G.shape[0], ctypes.c_float(lr), ld,
+                                                     _p(peers, _i32p), dp, N, P, S, R, col0, ncols)
+    if rc:
+        raise ValueError("combo_ref_local_sgd_steps_then_gossip rejected the arguments")
     return Y

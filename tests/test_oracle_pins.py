@@ -464,3 +464,43 @@ def test_planted_mistakes_are_caught(ref):
     transposed = np.stack([np.concatenate([(X[w, :3] + X[peers[w, 1, 0], :3]) / 2,
                                            (X[w, 3:] + X[peers[w, 0, 0], 3:]) / 2]) for w in range(3)])
     assert not np.array_equal(good, no_self) and not np.array_equal(good, transposed)
+
+
+# ------------------------------------------- several local steps (interval tau), then a round
+def test_multi_step_tau1_is_the_single_step(ref):
+    N, P, S, R = 6, 999, 7, 3
+    rng = np.random.default_rng(20)
+    X = rng.uniform(-0.1, 0.1, (N, P)).astype(np.float32)
+    G = rng.normal(0, 1e-2, (1, N, P)).astype(np.float32)
+    peers = ref.make_peer_table(N, S, R, 0, 0)
+    a, b = X.copy(), X.copy()
+    ya = ref.local_sgd_steps_then_gossip(a, G, 0.01, peers, P, S, R)
+    yb = ref.local_sgd_then_gossip(b, np.ascontiguousarray(G[0]), 0.01, peers, P, S, R)
+    assert np.array_equal(ya, yb) and np.array_equal(a, b)
+    # tau = 0: no local step at all
+    c = X.copy()
+    y0 = ref.local_sgd_steps_then_gossip(c, G[:0], 0.01, peers, P, S, R)
+    assert np.array_equal(y0, ref.gossip_round(X, peers, P, S, R)) and np.array_equal(c, X)
+
+
+def test_multi_step_equals_numpy_float32_passes(ref):
+    """tau elementwise binary32 passes x <- x - lr*g done by numpy (IEEE multiply and
+    subtract, no fusion), in step order, then the pinned round."""
+    N, P, S, R, tau = 5, 1003, 4, 2, 4
+    rng = np.random.default_rng(21)
+    X = rng.uniform(-0.1, 0.1, (N, P)).astype(np.float32)
+    G = rng.normal(0, 1.0, (tau, N, P)).astype(np.float32)
+    lr = np.float32(0.1)
+    peers = ref.make_peer_table(N, S, R, 1, 1)
+    Xs = X.copy()
+    for k in range(tau):
+        Xs = Xs - lr * G[k]
+        assert Xs.dtype == np.float32
+    Xc = X.copy()
+    Y = ref.local_sgd_steps_then_gossip(Xc, G, float(lr), peers, P, S, R)
+    assert np.array_equal(Xc, Xs)
+    assert np.array_equal(Y, ref.gossip_round(Xs, peers, P, S, R))
+    # order of the steps matters in binary32: reversing the gradients changes some bits
+    Xr = X.copy()
+    ref.local_sgd_steps_then_gossip(Xr, np.ascontiguousarray(G[::-1]), float(lr), peers, P, S, R)
+    assert not np.array_equal(Xr, Xs) and np.allclose(Xr, Xs, rtol=0, atol=1e-6)
