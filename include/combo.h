@@ -125,6 +125,20 @@ int combo_segment_gossip_round(float* d_dst, const float* d_src, int64_t ld,
                                int32_t N, int64_t P, int32_t S, int32_t R, void* stream);
 
 /*
+ * The same with a communication interval tau (Sec. 4.1 step 1: several SGD rounds between
+ * two synchronisations): tau steps x <- x - lr*g_t, t = 0..tau-1 in that order, each with
+ * its own given gradient, then the round on the result.
+ *   d_grads  in, device, float32[tau][N][ld]: slice t starts at d_grads + t*N*ld.
+ *   tau      >= 0; 0 is the plain round (d_grads may then be NULL).
+ * d_src as in combo_local_sgd_then_gossip (which is this call with tau = 1).
+ * Errors: as combo_local_sgd_then_gossip, plus COMBO_EINVAL for tau < 0.
+ */
+int combo_local_sgd_steps_then_gossip(float* d_dst, float* d_src, const float* d_grads,
+                                      int32_t tau, float lr, int64_t ld, const int32_t* d_peers,
+                                      const float* d_dataset_sizes, int32_t N, int64_t P,
+                                      int32_t S, int32_t R, void* stream);
+
+/*
  * Dynamic workers (Sec. 4.2).  d_status is device uint8[N]: 0 = offline, 1 = active,
  * 2 = newcomer joining in this round.
  *

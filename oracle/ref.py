@@ -79,6 +79,12 @@ def _check2d(a, dtype, name):
     return a.strides[0] // a.itemsize
 
 
+def _out_like(X, ld):
+    """float32 output with X's shape and row pitch."""
+    N, ncols = X.shape
+    return np.empty((N, ld), np.float32)[:, :ncols]
+
+
 def segment_bounds(P, S):
     lo = np.empty(S, np.int64)
     hi = np.empty(S, np.int64)
@@ -158,7 +164,7 @@ def make_peer_table_dynamic(status, N, S, R, seed, rnd):
 def gossip_round_dynamic(X, peers, status, P, S, R, d=None, col0=0):
     N, ncols = X.shape
     ld = _check2d(X, np.float32, "X")
-    Y = np.empty_like(X)
+    Y = _out_like(X, ld)
     if _check2d(Y, np.float32, "Y") != ld:
         raise ValueError("internal: pitch mismatch")
     peers = _peers_arg(peers, N, S, R)
@@ -192,7 +198,7 @@ def gossip_round(X, peers, P, S, R, d=None, col0=0, out=None):
     """fp32 round on a column window.  X: (N, ncols) float32 view (row pitch allowed)."""
     N, ncols = X.shape
     ld = _check2d(X, np.float32, "X")
-    Y = np.empty_like(X) if out is None else out
+    Y = _out_like(X, ld) if out is None else out
     ldy = _check2d(Y, np.float32, "Y")
     if ldy != ld or Y.shape != X.shape:
         raise ValueError("Y must have X's shape and pitch")
@@ -225,7 +231,7 @@ def local_sgd_then_gossip(X, G, lr, peers, P, S, R, d=None, col0=0):
     ldg = _check2d(G, np.float32, "G")
     if ldg != ld or G.shape != X.shape:
         raise ValueError("G must have X's shape and pitch")
-    Y = np.empty_like(X)
+    Y = _out_like(X, ld)
     if _check2d(Y, np.float32, "Y") != ld:
         raise ValueError("internal: pitch mismatch")
     peers = _peers_arg(peers, N, S, R)
@@ -243,10 +249,10 @@ def local_sgd_steps_then_gossip(X, G, lr, peers, P, S, R, d=None, col0=0):
     times, then returns the round on the stepped X."""
     N, ncols = X.shape
     ld = _check2d(X, np.float32, "X")
-    if not (G.dtype == np.float32 and G.ndim == 3 and G.shape[1:] == X.shape
-            and G.strides == (N * ld * 4, ld * 4, 4)):
+    if G.shape[0] > 0 and not (G.dtype == np.float32 and G.ndim == 3 and G.shape[1:] == X.shape
+                               and G.strides == (N * ld * 4, ld * 4, 4)):
         raise ValueError("G must be (tau, N, ncols) float32 with X's pitch and slice stride N*ld")
-    Y = np.empty_like(X)
+    Y = _out_like(X, ld)
     peers = _peers_arg(peers, N, S, R)
     dk, dp = _d_arg(d, N)
     rc = lib().combo_ref_local_sgd_steps_then_gossip(_p(Y, _f32p), _p(X, _f32p), _p(G, _f32p),

@@ -13,7 +13,7 @@ TUNE_FUSED_MODE = 2
 TUNE_KERNEL = 3
 TUNE_SLAB_COLS = 4
 
-EXPORTS = ("combo_aggregation_divergence", "combo_aggregation_divergence_workspace",
+EXPORTS = ("combo_local_sgd_steps_then_gossip", "combo_aggregation_divergence", "combo_aggregation_divergence_workspace",
            "combo_make_peer_table_dynamic", "combo_segment_gossip_round_dynamic",
            "combo_make_peer_table", "combo_make_peer_table_pooled", "combo_peer_in_degree", "combo_segment_gossip_round", "combo_local_sgd_then_gossip",
            "combo_tune", "combo_get_tune", "combo_strerror")
@@ -55,6 +55,9 @@ def lib():
         L.combo_segment_gossip_round.restype = ctypes.c_int
         L.combo_local_sgd_then_gossip.argtypes = [vp, vp, vp, f32, i64, vp, vp, i32, i64, i32, i32, vp]
         L.combo_local_sgd_then_gossip.restype = ctypes.c_int
+        L.combo_local_sgd_steps_then_gossip.argtypes = [vp, vp, vp, i32, f32, i64, vp, vp, i32, i64,
+                                                        i32, i32, vp]
+        L.combo_local_sgd_steps_then_gossip.restype = ctypes.c_int
         L.combo_tune.argtypes = [ctypes.c_int, ctypes.c_int]
         L.combo_tune.restype = ctypes.c_int
         L.combo_get_tune.argtypes = [ctypes.c_int]
@@ -228,4 +231,27 @@ def local_sgd_then_gossip(dst, src, grad, lr, peers, P, S, R, dataset_sizes=None
         N, P, S, R, _stream_ptr(stream))
     if rc:
         raise ComboError(rc, "combo_local_sgd_then_gossip")
+    return dst
+
+
+def local_sgd_steps_then_gossip(dst, src, grads, lr, peers, P, S, R, dataset_sizes=None, stream=None):
+    """combo_local_sgd_steps_then_gossip: grads is a (tau, N, ld)-strided float32 device
+    tensor (slice stride N*ld); tau = grads.shape[0]."""
+    N = src.shape[0]
+    ld = _matrix(src, "src")
+    if _matrix(dst, "dst") != ld or dst.shape[0] != N:
+        raise ValueError("dst must have src's row count and pitch")
+    tau = grads.shape[0]
+    if tau > 0 and not (grads.dim() == 3 and grads.shape[1] == N and grads.stride(2) == 1
+                        and (N == 1 or grads.stride(1) == ld)
+                        and (tau == 1 or grads.stride(0) == N * ld)):
+        raise ValueError("grads: need (tau, N, .) float32 with src's pitch and slice stride N*ld")
+    rc = lib().combo_local_sgd_steps_then_gossip(
+        _dev_ptr(dst, torch.float32, "dst"), _dev_ptr(src, torch.float32, "src"),
+        _dev_ptr(grads, torch.float32, "grads") if tau > 0 else None, tau, ctypes.c_float(lr), ld,
+        _dev_ptr(peers, torch.int32, "peers", optional=(R == 0)),
+        _dev_ptr(dataset_sizes, torch.float32, "dataset_sizes", optional=True),
+        N, P, S, R, _stream_ptr(stream))
+    if rc:
+        raise ComboError(rc, "combo_local_sgd_steps_then_gossip")
     return dst

@@ -43,7 +43,8 @@ int check_round_args(const float* dst, const float* src, int64_t ld, const int32
 // fused_in_round().
 int enqueue_round(float* dst, const float* src, const float* grad, float lr, int64_t ld,
                   const int32_t* peers, const float* dsz, int32_t N, int64_t P, int32_t S,
-                  int32_t R, Plan plan, hipStream_t st, const uint8_t* status = nullptr) {
+                  int32_t R, Plan plan, hipStream_t st, const uint8_t* status = nullptr,
+                  int32_t tau = 1) {
     const int tile_cols = g_tile_cols.load();
     const bool swizzle = g_swizzle.load() != 0;
     combo::RoundArgs a;
@@ -64,6 +65,8 @@ int enqueue_round(float* dst, const float* src, const float* grad, float lr, int
     a.p32 = P < (int64_t)0x100000000ll ? 1 : 0;
     a.inv = 1.0f / (float)(R + 1);
     a.lr = lr;
+    a.tau = tau;
+    a.grad_slice = (int64_t)N * ld;
     if (plan.kind == kPlanSlab)
         return combo::launch_round_slab(a, plan.cols, st) == hipSuccess ? COMBO_OK : COMBO_EHIP;
     if (status != nullptr)
@@ -158,29 +161,45 @@ int combo_segment_gossip_round_dynamic(float* d_dst, const float* d_src, int64_t
                          (hipStream_t)stream, d_status);
 }
 
-int combo_local_sgd_then_gossip(float* d_dst, float* d_src, const float* d_grad, float lr,
-                                int64_t ld, const int32_t* d_peers, const float* d_dataset_sizes,
-                                int32_t N, int64_t P, int32_t S, int32_t R, void* stream) {
+int combo_local_sgd_steps_then_gossip(float* d_dst, float* d_src, const float* d_grads, int32_t tau,
+                                      float lr, int64_t ld, const int32_t* d_peers,
+                                      const float* d_dataset_sizes, int32_t N, int64_t P, int32_t S,
+                                      int32_t R, void* stream) {
     const int rc = check_round_args(d_dst, d_src, ld, d_peers, N, P, S, R);
     if (rc != COMBO_OK) return rc;
-    if (d_grad == nullptr) return COMBO_EINVAL;
+    if (tau < 0 || (tau > 0 && d_grads == nullptr)) return COMBO_EINVAL;
     const uint64_t bytes = (uint64_t)N * (uint64_t)ld * sizeof(float);
-    if (overlaps(d_grad, bytes, d_src, bytes) || overlaps(d_grad, bytes, d_dst, bytes))
+    if (tau > 0 && (overlaps(d_grads, bytes * (uint64_t)tau, d_src, bytes) ||
+                    overlaps(d_grads, bytes * (uint64_t)tau, d_dst, bytes)))
         return COMBO_EALIAS;
-    const Plan plan = plan_for(d_dst, d_src, d_grad, ld, N, P, R);
-    if (plan.kind != kPlanTile && g_fused_mode.load() == 0)   // step folded into the slab fill
-        return enqueue_round(d_dst, d_src, d_grad, lr, ld, d_peers, d_dataset_sizes, N, P, S, R,
-                             plan, (hipStream_t)stream);
-    // two passes: step every row in place, then the plain round on the stepped buffer
+    const hipStream_t st = (hipStream_t)stream;
+    const Plan plan = plan_for(d_dst, d_src, d_grads, ld, N, P, R);
+    if (tau == 0)   // no local step: the plain round
+        return enqueue_round(d_dst, d_src, nullptr, 0.0f, ld, d_peers, d_dataset_sizes, N, P, S, R,
+                             plan, st);
+    if (plan.kind != kPlanTile && g_fused_mode.load() == 0)   // steps folded into the slab fill
+        return enqueue_round(d_dst, d_src, d_grads, lr, ld, d_peers, d_dataset_sizes, N, P, S, R,
+                             plan, st, nullptr, tau);
+    // separate passes: step every row in place tau times, then the plain round
     if ((plan.kind == kPlanTile &&
          combo::round_grid_size(N, P, g_tile_cols.load(), g_swizzle.load() != 0) == 0) ||
         combo::round_grid_size(N, P, 4096, false) == 0)
         return COMBO_ERANGE;
-    const bool vec = aligned16(d_src) && aligned16(d_grad) && (ld % 4 == 0);
-    if (combo::launch_sgd_step(d_src, d_grad, lr, ld, N, P, vec, (hipStream_t)stream) != hipSuccess)
-        return COMBO_EHIP;
+    const bool vec = aligned16(d_src) && aligned16(d_grads) && (ld % 4 == 0);
+    for (int32_t t = 0; t < tau; ++t)
+        if (combo::launch_sgd_step(d_src, d_grads + (size_t)t * (size_t)N * (size_t)ld, lr, ld, N, P,
+                                   vec, st) != hipSuccess)
+            return COMBO_EHIP;
     return enqueue_round(d_dst, d_src, nullptr, 0.0f, ld, d_peers, d_dataset_sizes, N, P, S, R, plan,
-                         (hipStream_t)stream);
+                         st);
+}
+
+int combo_local_sgd_then_gossip(float* d_dst, float* d_src, const float* d_grad, float lr,
+                                int64_t ld, const int32_t* d_peers, const float* d_dataset_sizes,
+                                int32_t N, int64_t P, int32_t S, int32_t R, void* stream) {
+    if (d_grad == nullptr) return COMBO_EINVAL;
+    return combo_local_sgd_steps_then_gossip(d_dst, d_src, d_grad, 1, lr, ld, d_peers,
+                                             d_dataset_sizes, N, P, S, R, stream);
 }
 
 int64_t combo_aggregation_divergence_workspace(int32_t N, int64_t P) {

@@ -28,6 +28,8 @@ struct RoundArgs {
     int32_t p32;             // 1: P < 2^32, segment lookup may divide in 32 bits
     float inv;               // 1.0f / (float)(R + 1)
     float lr;                // learning rate of the fused local step
+    int32_t tau;             // number of fused local steps (gradient slices)
+    int64_t grad_slice;      // elements between consecutive gradient slices (N * ld)
 };
 
 // launchers (defined in gossip_round.hip / peer_table.hip); return hipGetLastError()

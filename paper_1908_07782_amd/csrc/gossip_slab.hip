@@ -10,9 +10,10 @@
 // back buffer with non-temporal 128-bit stores.  HBM and L2 see one read and one write
 // per element whatever R is; the R+1 reads per output are LDS reads.
 //
-// With the local step fused in, the slab is filled with x - lr*g (gradient read once,
-// product rounded before the difference), so peers are served post-update values as
-// Sec. 4.1 requires, and the front buffer itself is left untouched.
+// With the local update fused in, the slab is filled with the parameters after the tau
+// SGD steps x <- x - lr*g_t (each gradient slice read once, product rounded before the
+// difference, slices in order), so peers are served post-update values as Sec. 4.1
+// requires, and the front buffer itself is left untouched.  (Callers pass tau >= 1.)
 //
 // A strip that contains a segment boundary or the ragged end of the row (at most S
 // strips per round) falls back to per-element evaluation from global memory.
@@ -68,21 +69,40 @@ __global__ __launch_bounds__(kSlabThreads) void gossip_slab_kernel(const RoundAr
 
         for (int base = 0; base < total4; base += kSlabThreads * kBatch) {
             v4f x[kBatch], g[kBatch];
+            size_t off[kBatch];
 #pragma unroll
             for (int u = 0; u < kBatch; ++u) {
                 const int idx = base + u * kSlabThreads + (int)threadIdx.x;
                 if (idx < total4) {
                     const int row = idx >> w4_shift;
                     const int c4 = idx & (W4 - 1);
-                    const size_t off = (size_t)row * (size_t)a.ld + (size_t)col0 + (size_t)c4 * 4;
-                    x[u] = load4_slab(a.src + off);
-                    if (FUSED) g[u] = load4_slab(a.grad + off);
+                    off[u] = (size_t)row * (size_t)a.ld + (size_t)col0 + (size_t)c4 * 4;
+                    x[u] = load4_slab(a.src + off[u]);
+                    if (FUSED) g[u] = load4_slab(a.grad + off[u]);
+                }
+            }
+            if (FUSED) {
+                // local steps in slice order; the first slice's loads are already in flight
+                for (int32_t t = 0; t < a.tau; ++t) {
+                    if (t > 0) {
+#pragma unroll
+                        for (int u = 0; u < kBatch; ++u) {
+                            const int idx = base + u * kSlabThreads + (int)threadIdx.x;
+                            if (idx < total4)
+                                g[u] = load4_slab(a.grad + (size_t)t * (size_t)a.grad_slice + off[u]);
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < kBatch; ++u) {
+                        const int idx = base + u * kSlabThreads + (int)threadIdx.x;
+                        if (idx < total4) x[u] = sgd_step4(x[u], a.lr, g[u]);
+                    }
                 }
             }
 #pragma unroll
             for (int u = 0; u < kBatch; ++u) {
                 const int idx = base + u * kSlabThreads + (int)threadIdx.x;
-                if (idx < total4) slab[idx] = FUSED ? sgd_step4(x[u], a.lr, g[u]) : x[u];
+                if (idx < total4) slab[idx] = x[u];
             }
         }
         __syncthreads();

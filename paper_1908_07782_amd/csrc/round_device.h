@@ -64,12 +64,15 @@ __device__ __forceinline__ int32_t segment_of(int64_t e, const RoundArgs& a) {
 }
 
 // pre-aggregation value of worker `row` at column e: the stored parameter, or, when the
-// local step is fused in, the parameter after one SGD step
+// local steps are fused in, the parameter after the tau SGD steps (in slice order)
 template <bool FUSED>
 __device__ __forceinline__ float served_value(const RoundArgs& a, int32_t row, int64_t e) {
     const size_t k = (size_t)row * (size_t)a.ld + (size_t)e;
-    if (FUSED) return sgd_step(a.src[k], a.lr, a.grad[k]);
-    return a.src[k];
+    float x = a.src[k];
+    if (FUSED)
+        for (int32_t t = 0; t < a.tau; ++t)
+            x = sgd_step(x, a.lr, a.grad[(size_t)t * (size_t)a.grad_slice + k]);
+    return x;
 }
 
 // Eq. (3) for one element of any segment: used for tiles that contain a segment

@@ -404,3 +404,35 @@ def test_runs_on_a_side_stream(combo, ref):
     st.synchronize()
     ph = ref.make_peer_table(N, S, R, 5, 6)
     assert_params_match(dst[:, :P].cpu().numpy(), ref.gossip_round(Xh, ph, P, S, R))
+
+
+# ------------------------------------------ several local steps (interval tau), then the round
+@pytest.mark.parametrize("tau", [0, 1, 3])
+@pytest.mark.parametrize("mode", ["fused_slab", "two_pass_slab", "two_pass_tile"])
+@pytest.mark.parametrize("N,P,S,R,weighted", [(6, 10_007, 7, 3, False), (32, 40_000, 32, 4, True),
+                                              (100, 5_003, 7, 3, False)])
+def test_multi_step_local_update(combo, ref, tau, mode, N, P, S, R, weighted):
+    combo.tune(combo.TUNE_FUSED_MODE, 0 if mode.startswith("fused") else 1)
+    combo.tune(combo.TUNE_KERNEL, 1 if mode == "two_pass_tile" else 0)
+    lr = 0.05
+    rng = np.random.default_rng(tau * 100 + N)
+    ld = combo.workloads.row_pitch(P)
+    Xh = rng.uniform(-0.1, 0.1, (N, P)).astype(np.float32)
+    Gh = np.zeros((tau, N, ld), np.float32)
+    Gh[:, :, :P] = rng.normal(0, 1e-2, (tau, N, P)).astype(np.float32)
+    buf = torch.full((2, N, ld), float("nan"), dtype=torch.float32, device="cuda")
+    buf[0, :, :P] = torch.from_numpy(Xh).cuda()
+    grads = torch.from_numpy(Gh).cuda()
+    peers = device_table(combo, N, S, R, 2, 3)
+    d = combo.workloads.dataset_sizes(N, 1, "cuda") if weighted else None
+    combo.local_sgd_steps_then_gossip(buf[1], buf[0], grads, lr, peers, P, S, R, dataset_sizes=d)
+    torch.cuda.synchronize()
+    ph = ref.make_peer_table(N, S, R, 2, 3)
+    Xs = np.zeros((N, ld), np.float32)
+    Xs[:, :P] = Xh
+    want = ref.local_sgd_steps_then_gossip(Xs[:, :P], Gh[:, :, :P], lr, ph, P, S, R,
+                                           d=None if d is None else d.cpu().numpy())
+    assert_params_match(buf[1, :, :P].cpu().numpy(), want, f"tau={tau} {mode}")
+    front = buf[0, :, :P].cpu().numpy()
+    assert_params_match(front, Xh if (mode.startswith("fused") or tau == 0) else Xs[:, :P], "front buffer")
+    assert bool(torch.isnan(buf[:, :, P:]).all())
