@@ -74,6 +74,98 @@ def cpu_baseline(wl, X0_host, budget_s=15.0):
                       f"columns), single thread, {dt:.1f} s"}
 
 
+def time_kernel(fn, stream, reps=20, warm=3):
+    """Average milliseconds of fn() (which enqueues on `stream`), HIP events."""
+    import torch
+    for _ in range(warm):
+        fn()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record(stream)
+    for _ in range(reps):
+        fn()
+    b.record(stream)
+    b.synchronize()
+    return a.elapsed_time(b) / reps
+
+
+def sweep_paper(combo, P):
+    """The paper's own sweeps as bandwidth curves (Sec. 5.2: 30 workers; R = 1..16 at
+    S = 10; S = 1..10 at R = 2).  One JSON line per point."""
+    import torch
+    N = 30
+    ld = combo.workloads.row_pitch(P)
+    wl = combo.workloads.small_case(N, P, 10, 2, scale=0.02)
+    arena = torch.zeros((2, N, ld), dtype=torch.float32, device="cuda")
+    combo.workloads.fill_params(arena[0], wl)
+    stream = torch.cuda.current_stream()
+    points = [("R", 10, r) for r in (1, 2, 3, 4, 6, 8, 12, 16, 29)] + \
+             [("S", s, 2) for s in (1, 2, 3, 4, 6, 8, 10)]
+    for which, S, R in points:
+        peers = torch.empty(N * S * R, dtype=torch.int32, device="cuda")
+        combo.make_peer_table(peers, N, S, R, 0, 0)
+        ms = time_kernel(lambda: combo.segment_gossip_round(arena[1], arena[0], peers, P, S, R,
+                                                            stream=stream), stream)
+        print(json.dumps({"sweep": which, "N": N, "P": P, "S": S, "R": R, "kernel_ms": ms,
+                          "rounds_per_s": 1e3 / ms,
+                          "effective_GBs": 4 * (R + 2) * N * P / ms / 1e6,
+                          "compulsory_GBs": 8 * N * P / ms / 1e6}), flush=True)
+
+
+def extras(combo, wl):
+    """Timings of the other entry points on the workload's shape.  One JSON line each."""
+    import torch
+    N, P, S, R, ld = wl.N, wl.P, wl.S, wl.R, wl.ld
+    arena = torch.zeros((2, N, ld), dtype=torch.float32, device="cuda")
+    combo.workloads.fill_params(arena[0], wl)
+    stream = torch.cuda.current_stream()
+    peers = torch.empty(N * S * R, dtype=torch.int32, device="cuda")
+
+    def emit(name, ms, nbytes=None, **kw):
+        rec = {"op": name, "workload": wl.name, "ms": ms}
+        if nbytes:
+            rec["GBs"] = nbytes / ms / 1e6
+        rec.update(kw)
+        print(json.dumps(rec), flush=True)
+
+    emit("combo_make_peer_table", time_kernel(
+        lambda: combo.make_peer_table(peers, N, S, R, 0, 1, stream=stream), stream))
+    emit("combo_make_peer_table_pooled", time_kernel(
+        lambda: combo.make_peer_table_pooled(peers, N, S, R, 0, 1, stream=stream), stream))
+    deg = torch.empty(N, dtype=torch.int32, device="cuda")
+    emit("combo_peer_in_degree", time_kernel(
+        lambda: combo.peer_in_degree(deg, peers, N, S, R, stream=stream), stream))
+    # aggregation divergence: read-only pass, 4 bytes per element
+    ws = torch.empty(combo.aggregation_divergence_workspace(N, P) // 8, dtype=torch.float64, device="cuda")
+    d2 = torch.empty(N, dtype=torch.float64, device="cuda")
+    emit("combo_aggregation_divergence", time_kernel(
+        lambda: combo.aggregation_divergence(d2, arena[0], P, ws, stream=stream), stream),
+        4 * N * P, note="bytes = one read of every element")
+    # dynamic round with every tenth worker offline and one newcomer
+    st = torch.ones(N, dtype=torch.uint8)
+    st[::10] = 0
+    st[1] = 2
+    st = st.cuda()
+    combo.make_peer_table_dynamic(peers, st, N, S, R, 0, 1)
+    emit("combo_segment_gossip_round_dynamic", time_kernel(
+        lambda: combo.segment_gossip_round_dynamic(arena[1], arena[0], peers, st, P, S, R,
+                                                   stream=stream), stream),
+        8 * N * P, note="bytes = compulsory read + write")
+    combo.make_peer_table(peers, N, S, R, 0, 1)
+    dsz = combo.workloads.dataset_sizes(N, 0, "cuda")
+    emit("combo_segment_gossip_round (dataset-size weights)", time_kernel(
+        lambda: combo.segment_gossip_round(arena[1], arena[0], peers, P, S, R, dataset_sizes=dsz,
+                                           stream=stream), stream), 8 * N * P,
+        note="bytes = compulsory read + write")
+    for tau in (1, 2, 4):
+        grads = torch.zeros((tau, N, ld), dtype=torch.float32, device="cuda")
+        grads.normal_(0, 1e-3)
+        emit(f"combo_local_sgd_steps_then_gossip tau={tau}", time_kernel(
+            lambda: combo.local_sgd_steps_then_gossip(arena[1], arena[0], grads, 0.01, peers, P, S, R,
+                                                      stream=stream), stream),
+            (8 + 4 * tau) * N * P, note="bytes = x read + tau gradient reads + write")
+        del grads
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -89,6 +181,10 @@ def main():
                     help="override R (0 turns the round into a plain copy of known size: the "
                          "calibration kernel for the HBM byte counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep-paper", action="store_true",
+                    help="instead of the benchmark line: the paper's R and S sweeps (30 workers)")
+    ap.add_argument("--extras", action="store_true",
+                    help="instead of the benchmark line: timings of the other entry points")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (all N simulated workers live in one "
@@ -115,6 +211,10 @@ def main():
         wl = dataclasses.replace(wl, R=args.replicas, name=f"{wl.name}_R{args.replicas}")
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.sweep_paper:
+        return sweep_paper(combo, wl.P)
+    if args.extras:
+        return extras(combo, wl)
 
     arena = torch.zeros((2, wl.N, wl.ld), dtype=torch.float32, device=dev)
     combo.workloads.fill_params(arena[0], wl)

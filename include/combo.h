@@ -203,7 +203,7 @@ int combo_local_sgd_then_gossip(float* d_dst, float* d_src, const float* d_grad,
  *                combo_aggregation_divergence_workspace(N, P) bytes; contents irrelevant
  *                before and after the call
  * Errors: COMBO_EINVAL for bad sizes, NULL pointers, a workspace that is too small or
- * misaligned; COMBO_ERANGE when N rows of a 64-column strip do not fit in LDS (N > ~250).
+ * misaligned; COMBO_ERANGE when N rows of a 64-column strip do not fit in LDS (N > ~230).
  * combo_aggregation_divergence_workspace returns the byte count, or a negative status.
  */
 int64_t combo_aggregation_divergence_workspace(int32_t N, int64_t P);

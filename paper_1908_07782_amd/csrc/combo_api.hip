@@ -206,7 +206,7 @@ int64_t combo_aggregation_divergence_workspace(int32_t N, int64_t P) {
     if (N < 1 || P < 1) return COMBO_EINVAL;
     const int W = combo::divergence_strip_cols(N);
     if (W == 0) return COMBO_ERANGE;
-    return (int64_t)combo::divergence_grid(P, W) * (int64_t)N * (int64_t)sizeof(double);
+    return (int64_t)combo::divergence_grid(N, P, W) * (int64_t)N * (int64_t)sizeof(double);
 }
 
 int combo_aggregation_divergence(double* d_dist2, const float* d_x, int64_t ld,

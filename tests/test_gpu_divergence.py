@@ -31,7 +31,7 @@ def gpu_divergence(combo, x, P, d=None):
 
 
 @pytest.mark.parametrize("N,P", [(4, 65_536), (12, 30_001), (32, 200_003), (100, 50_003), (1, 5_000),
-                                 (2, 63), (240, 4_097), (16, 1_000_000)])
+                                 (2, 63), (224, 4_097), (16, 1_000_000)])
 @pytest.mark.parametrize("weighted", [False, True])
 def test_divergence_matches_oracle(combo, ref, N, P, weighted):
     rng = np.random.default_rng(N * 7 + P)
