@@ -32,10 +32,11 @@ def kernel_source_digest():
     return h.hexdigest()[:16]
 
 
-def recorded_traffic(workload):
+def recorded_traffic(workload, layout):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc
     summary, or None when there is none or the kernel source changed since."""
-    path = os.path.join(ROOT, "profiles", f"gossip_slab_kernel_{workload}_pmc.txt")
+    tag = "" if layout == "rows" else "_tiled"
+    path = os.path.join(ROOT, "profiles", f"gossip_slab_kernel_{workload}{tag}_pmc.txt")
     if not os.path.exists(path):
         return None
     text = open(path).read()
@@ -180,6 +181,9 @@ def main():
     ap.add_argument("--replicas", type=int, default=-1,
                     help="override R (0 turns the round into a plain copy of known size: the "
                          "calibration kernel for the HBM byte counters)")
+    ap.add_argument("--layout", choices=["rows", "tiled"], default="rows",
+                    help="arena layout: row-major [N][ld] or tiled [T][N][Wt]")
+    ap.add_argument("--tiled-cols", type=int, default=0, help="tile width of the tiled layout")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep-paper", action="store_true",
                     help="instead of the benchmark line: the paper's R and S sweeps (30 workers)")
@@ -216,16 +220,27 @@ def main():
     if args.extras:
         return extras(combo, wl)
 
-    arena = torch.zeros((2, wl.N, wl.ld), dtype=torch.float32, device=dev)
-    combo.workloads.fill_params(arena[0], wl)
-    grads = None
-    if wl.fused:
-        grads = torch.zeros((wl.N, wl.ld), dtype=torch.float32, device=dev)
-        combo.workloads.fill_grads(grads, wl, 0)
-    peers = torch.empty(max(wl.N * wl.S * wl.R, 1), dtype=torch.int32, device=dev)
+    tiled = args.layout == "tiled"
+    Wt = (args.tiled_cols or combo.tiled_cols(wl.N, wl.R)) if tiled else 0
+    rows = torch.zeros((wl.N, wl.ld), dtype=torch.float32, device=dev)
+    combo.workloads.fill_params(rows, wl)
     X0_host = None
     if not args.no_cpu_baseline:
-        X0_host = arena[0, :, :wl.P].cpu().numpy()
+        X0_host = rows[:, :wl.P].cpu().numpy()
+    if tiled:
+        n = combo.tiled_elems(wl.N, wl.P, Wt)
+        arena = torch.zeros((2, n), dtype=torch.float32, device=dev)
+        combo.pack_tiled(arena[0], rows, wl.N, wl.P, Wt)
+        del rows
+    else:
+        arena = torch.zeros((2, wl.N, wl.ld), dtype=torch.float32, device=dev)
+        arena[0].copy_(rows)
+        del rows
+    grads = None
+    if wl.fused:
+        grads = torch.zeros_like(arena[0])
+        grads.normal_(0.0, wl.grad_std)          # layout-agnostic: i.i.d. values
+    peers = torch.empty(max(wl.N * wl.S * wl.R, 1), dtype=torch.int32, device=dev)
     stream = torch.cuda.current_stream()
 
     state = {"cur": 0, "round": 0}
@@ -235,7 +250,13 @@ def main():
         combo.make_peer_table(peers, wl.N, wl.S, wl.R, wl.hash_seed, rnd, stream=stream)
         if ev is not None:
             ev[0].record(stream)
-        if wl.fused:
+        if tiled and wl.fused:
+            combo.local_sgd_steps_then_gossip_tiled(arena[1 - cur], arena[cur], grads, 1, wl.lr, Wt,
+                                                    peers, wl.N, wl.P, wl.S, wl.R, stream=stream)
+        elif tiled:
+            combo.segment_gossip_round_tiled(arena[1 - cur], arena[cur], Wt, peers, wl.N, wl.P, wl.S,
+                                             wl.R, stream=stream)
+        elif wl.fused:
             combo.local_sgd_then_gossip(arena[1 - cur], arena[cur], grads, wl.lr, peers, wl.P, wl.S,
                                         wl.R, stream=stream)
         else:
@@ -264,12 +285,12 @@ def main():
     # g and a write of x
     alg_bytes = wl.algorithmic_bytes_per_round
     if wl.fused:
-        fused_in_kernel = combo.get_tune(combo.TUNE_KERNEL) != 1 and \
-            combo.get_tune(combo.TUNE_FUSED_MODE) == 0
+        fused_in_kernel = tiled or (combo.get_tune(combo.TUNE_KERNEL) != 1 and
+                                    combo.get_tune(combo.TUNE_FUSED_MODE) == 0)
         alg_bytes += 4 * wl.N * wl.P * (1 if fused_in_kernel else 3)
     achieved = alg_bytes / (kern_avg_ms * 1e-3) / 1e9
-    slab = combo.get_tune(combo.TUNE_KERNEL) != 1
-    two_pass = wl.fused and (not slab or combo.get_tune(combo.TUNE_FUSED_MODE) == 1)
+    slab = tiled or combo.get_tune(combo.TUNE_KERNEL) != 1
+    two_pass = wl.fused and not tiled and (not slab or combo.get_tune(combo.TUNE_FUSED_MODE) == 1)
     kernel_name = ("gossip_slab_kernel" if slab else "gossip_round_kernel") + \
         (" (+ sgd_step_kernel)" if two_pass else "")
     out = {
@@ -286,7 +307,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": wl.name, "N": wl.N, "P": wl.P, "S": wl.S, "R": wl.R,
-                   "fused_local_step": wl.fused, "kernel": combo.get_tune(combo.TUNE_KERNEL),
+                   "fused_local_step": wl.fused, "layout": args.layout, "tiled_cols": Wt, "kernel": combo.get_tune(combo.TUNE_KERNEL),
                    "slab_cols": combo.get_tune(combo.TUNE_SLAB_COLS),
                    "fused_mode": combo.get_tune(combo.TUNE_FUSED_MODE),
                    "tile_cols": combo.get_tune(combo.TUNE_TILE_COLS),
@@ -300,7 +321,7 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": recorded_traffic(wl.name),
+            "traffic": recorded_traffic(wl.name, args.layout),
             "algorithmic_bytes_per_launch": alg_bytes,
             "compulsory_bytes_per_launch": 8 * wl.N * wl.P + (4 * wl.N * wl.P if wl.fused else 0),
             "kernel_ms_avg": kern_avg_ms,

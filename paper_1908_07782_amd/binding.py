@@ -13,7 +13,9 @@ TUNE_FUSED_MODE = 2
 TUNE_KERNEL = 3
 TUNE_SLAB_COLS = 4
 
-EXPORTS = ("combo_local_sgd_steps_then_gossip", "combo_aggregation_divergence", "combo_aggregation_divergence_workspace",
+EXPORTS = ("combo_tiled_cols", "combo_tiled_elems", "combo_pack_tiled", "combo_unpack_tiled",
+           "combo_segment_gossip_round_tiled", "combo_local_sgd_steps_then_gossip_tiled",
+           "combo_local_sgd_steps_then_gossip", "combo_aggregation_divergence", "combo_aggregation_divergence_workspace",
            "combo_make_peer_table_dynamic", "combo_segment_gossip_round_dynamic",
            "combo_make_peer_table", "combo_make_peer_table_pooled", "combo_peer_in_degree", "combo_segment_gossip_round", "combo_local_sgd_then_gossip",
            "combo_tune", "combo_get_tune", "combo_strerror")
@@ -58,6 +60,19 @@ def lib():
         L.combo_local_sgd_steps_then_gossip.argtypes = [vp, vp, vp, i32, f32, i64, vp, vp, i32, i64,
                                                         i32, i32, vp]
         L.combo_local_sgd_steps_then_gossip.restype = ctypes.c_int
+        L.combo_tiled_cols.argtypes = [i32, i32]
+        L.combo_tiled_cols.restype = ctypes.c_int32
+        L.combo_tiled_elems.argtypes = [i32, i64, i32]
+        L.combo_tiled_elems.restype = ctypes.c_int64
+        L.combo_pack_tiled.argtypes = [vp, vp, i64, i32, i64, i32, vp]
+        L.combo_pack_tiled.restype = ctypes.c_int
+        L.combo_unpack_tiled.argtypes = [vp, i64, vp, i32, i64, i32, vp]
+        L.combo_unpack_tiled.restype = ctypes.c_int
+        L.combo_segment_gossip_round_tiled.argtypes = [vp, vp, i32, vp, vp, vp, i32, i64, i32, i32, vp]
+        L.combo_segment_gossip_round_tiled.restype = ctypes.c_int
+        L.combo_local_sgd_steps_then_gossip_tiled.argtypes = [vp, vp, vp, i32, f32, i32, vp, vp, i32,
+                                                              i64, i32, i32, vp]
+        L.combo_local_sgd_steps_then_gossip_tiled.restype = ctypes.c_int
         L.combo_tune.argtypes = [ctypes.c_int, ctypes.c_int]
         L.combo_tune.restype = ctypes.c_int
         L.combo_get_tune.argtypes = [ctypes.c_int]
@@ -254,4 +269,73 @@ def local_sgd_steps_then_gossip(dst, src, grads, lr, peers, P, S, R, dataset_siz
         N, P, S, R, _stream_ptr(stream))
     if rc:
         raise ComboError(rc, "combo_local_sgd_steps_then_gossip")
+    return dst
+
+
+# ---- tiled arena layout [T][N][Wt] ----------------------------------------------------
+def tiled_cols(N, R):
+    w = lib().combo_tiled_cols(N, R)
+    if w < 0:
+        raise ComboError(int(w), "combo_tiled_cols")
+    return int(w)
+
+
+def tiled_elems(N, P, tile_cols):
+    n = lib().combo_tiled_elems(N, P, tile_cols)
+    if n < 0:
+        raise ComboError(int(n), "combo_tiled_elems")
+    return int(n)
+
+
+def _flat(t, n, name):
+    if not (t.is_contiguous() and t.numel() >= n):
+        raise ValueError(f"{name}: need a contiguous float32 device tensor of at least {n} elements")
+    return _dev_ptr(t, torch.float32, name)
+
+
+def pack_tiled(tiled, rows, N, P, tile_cols, stream=None):
+    """combo_pack_tiled: rows is an (N, ld)-strided matrix, tiled a flat buffer."""
+    ld = _matrix(rows, "rows")
+    rc = lib().combo_pack_tiled(_flat(tiled, tiled_elems(N, P, tile_cols), "tiled"),
+                                _dev_ptr(rows, torch.float32, "rows"), ld, N, P, tile_cols,
+                                _stream_ptr(stream))
+    if rc:
+        raise ComboError(rc, "combo_pack_tiled")
+    return tiled
+
+
+def unpack_tiled(rows, tiled, N, P, tile_cols, stream=None):
+    ld = _matrix(rows, "rows")
+    rc = lib().combo_unpack_tiled(_dev_ptr(rows, torch.float32, "rows"), ld,
+                                  _flat(tiled, tiled_elems(N, P, tile_cols), "tiled"), N, P, tile_cols,
+                                  _stream_ptr(stream))
+    if rc:
+        raise ComboError(rc, "combo_unpack_tiled")
+    return rows
+
+
+def segment_gossip_round_tiled(dst, src, tile_cols, peers, N, P, S, R, dataset_sizes=None,
+                               status=None, stream=None):
+    n = tiled_elems(N, P, tile_cols)
+    rc = lib().combo_segment_gossip_round_tiled(
+        _flat(dst, n, "dst"), _flat(src, n, "src"), tile_cols,
+        _dev_ptr(peers, torch.int32, "peers", optional=(R == 0)),
+        _dev_ptr(dataset_sizes, torch.float32, "dataset_sizes", optional=True),
+        _dev_ptr(status, torch.uint8, "status", optional=True), N, P, S, R, _stream_ptr(stream))
+    if rc:
+        raise ComboError(rc, "combo_segment_gossip_round_tiled")
+    return dst
+
+
+def local_sgd_steps_then_gossip_tiled(dst, src, grads, tau, lr, tile_cols, peers, N, P, S, R,
+                                      dataset_sizes=None, stream=None):
+    n = tiled_elems(N, P, tile_cols)
+    rc = lib().combo_local_sgd_steps_then_gossip_tiled(
+        _flat(dst, n, "dst"), _flat(src, n, "src"),
+        _flat(grads, n * tau, "grads") if tau > 0 else None, tau, ctypes.c_float(lr), tile_cols,
+        _dev_ptr(peers, torch.int32, "peers", optional=(R == 0)),
+        _dev_ptr(dataset_sizes, torch.float32, "dataset_sizes", optional=True),
+        N, P, S, R, _stream_ptr(stream))
+    if rc:
+        raise ComboError(rc, "combo_local_sgd_steps_then_gossip_tiled")
     return dst

@@ -44,7 +44,7 @@ int check_round_args(const float* dst, const float* src, int64_t ld, const int32
 int enqueue_round(float* dst, const float* src, const float* grad, float lr, int64_t ld,
                   const int32_t* peers, const float* dsz, int32_t N, int64_t P, int32_t S,
                   int32_t R, Plan plan, hipStream_t st, const uint8_t* status = nullptr,
-                  int32_t tau = 1) {
+                  int32_t tau = 1, int arena_tile = 0) {
     const int tile_cols = g_tile_cols.load();
     const bool swizzle = g_swizzle.load() != 0;
     combo::RoundArgs a;
@@ -66,7 +66,13 @@ int enqueue_round(float* dst, const float* src, const float* grad, float lr, int
     a.inv = 1.0f / (float)(R + 1);
     a.lr = lr;
     a.tau = tau;
+    a.tile_shift = 0;
     a.grad_slice = (int64_t)N * ld;
+    if (arena_tile) {         // tiled arena [T][N][Wt]
+        while ((1 << a.tile_shift) < arena_tile) ++a.tile_shift;
+        const int64_t tiles = (P + arena_tile - 1) / arena_tile;
+        a.grad_slice = tiles * (int64_t)N * (int64_t)arena_tile;
+    }
     if (plan.kind == kPlanSlab)
         return combo::launch_round_slab(a, plan.cols, st) == hipSuccess ? COMBO_OK : COMBO_EHIP;
     if (status != nullptr)
@@ -200,6 +206,97 @@ int combo_local_sgd_then_gossip(float* d_dst, float* d_src, const float* d_grad,
     if (d_grad == nullptr) return COMBO_EINVAL;
     return combo_local_sgd_steps_then_gossip(d_dst, d_src, d_grad, 1, lr, ld, d_peers,
                                              d_dataset_sizes, N, P, S, R, stream);
+}
+
+// ---- tiled arena layout ---------------------------------------------------------------
+namespace {
+
+bool tile_cols_ok(int tile_cols) {
+    return tile_cols >= 64 && tile_cols <= 1024 && (tile_cols & (tile_cols - 1)) == 0;
+}
+
+int64_t tiled_elems(int32_t N, int64_t P, int tile_cols) {
+    return (P + tile_cols - 1) / tile_cols * (int64_t)N * (int64_t)tile_cols;
+}
+
+// argument checks shared by the tiled aggregation entry points
+int check_tiled_args(const float* dst, const float* src, int32_t tile_cols, const int32_t* peers,
+                     int32_t N, int64_t P, int32_t S, int32_t R) {
+    if (N < 1 || S < 1 || P < 1 || (int64_t)S > P || R < 0 || R > N - 1) return COMBO_EINVAL;
+    if (!tile_cols_ok(tile_cols) || dst == nullptr || src == nullptr) return COMBO_EINVAL;
+    if (R > 0 && peers == nullptr) return COMBO_EINVAL;
+    if (!aligned16(dst) || !aligned16(src)) return COMBO_EINVAL;
+    const uint64_t bytes = (uint64_t)tiled_elems(N, P, tile_cols) * sizeof(float);
+    if (overlaps(dst, bytes, src, bytes)) return COMBO_EALIAS;
+    if (combo::slab_strip_cols(N, R, tile_cols) != tile_cols) return COMBO_ERANGE;   // slab too big
+    if (((uint64_t)P + (uint64_t)tile_cols - 1) / (uint64_t)tile_cols > 0x7FFFFFFFull)
+        return COMBO_ERANGE;
+    return COMBO_OK;
+}
+
+}  // namespace
+
+int64_t combo_tiled_elems(int32_t N, int64_t P, int32_t tile_cols) {
+    if (N < 1 || P < 1 || !tile_cols_ok(tile_cols)) return COMBO_EINVAL;
+    return tiled_elems(N, P, tile_cols);
+}
+
+int32_t combo_tiled_cols(int32_t N, int32_t R) {
+    if (N < 1 || R < 0) return COMBO_EINVAL;
+    // 8 KiB slabs measured best; never below 64 columns (256-byte row chunks)
+    for (int W = 1024; W >= 64; W >>= 1)
+        if ((int64_t)N * W * 4 <= 8 * 1024 && combo::slab_strip_cols(N, R, W) == W) return W;
+    return combo::slab_strip_cols(N, R, 64) == 64 ? 64 : COMBO_ERANGE;
+}
+
+int combo_pack_tiled(float* d_tiled, const float* d_rows, int64_t ld, int32_t N, int64_t P,
+                     int32_t tile_cols, void* stream) {
+    if (N < 1 || P < 1 || ld < P || !tile_cols_ok(tile_cols) || d_tiled == nullptr ||
+        d_rows == nullptr)
+        return COMBO_EINVAL;
+    if (overlaps(d_tiled, (uint64_t)tiled_elems(N, P, tile_cols) * 4, d_rows,
+                 (uint64_t)N * (uint64_t)ld * 4))
+        return COMBO_EALIAS;
+    return combo::launch_pack_tiled(d_tiled, d_rows, ld, N, P, tile_cols, (hipStream_t)stream) ==
+                   hipSuccess ? COMBO_OK : COMBO_EHIP;
+}
+
+int combo_unpack_tiled(float* d_rows, int64_t ld, const float* d_tiled, int32_t N, int64_t P,
+                       int32_t tile_cols, void* stream) {
+    if (N < 1 || P < 1 || ld < P || !tile_cols_ok(tile_cols) || d_tiled == nullptr ||
+        d_rows == nullptr)
+        return COMBO_EINVAL;
+    if (overlaps(d_tiled, (uint64_t)tiled_elems(N, P, tile_cols) * 4, d_rows,
+                 (uint64_t)N * (uint64_t)ld * 4))
+        return COMBO_EALIAS;
+    return combo::launch_unpack_tiled(d_rows, ld, d_tiled, N, P, tile_cols, (hipStream_t)stream) ==
+                   hipSuccess ? COMBO_OK : COMBO_EHIP;
+}
+
+int combo_segment_gossip_round_tiled(float* d_dst, const float* d_src, int32_t tile_cols,
+                                     const int32_t* d_peers, const float* d_dataset_sizes,
+                                     const uint8_t* d_status, int32_t N, int64_t P, int32_t S,
+                                     int32_t R, void* stream) {
+    const int rc = check_tiled_args(d_dst, d_src, tile_cols, d_peers, N, P, S, R);
+    if (rc != COMBO_OK) return rc;
+    return enqueue_round(d_dst, d_src, nullptr, 0.0f, tile_cols, d_peers, d_dataset_sizes, N, P, S, R,
+                         Plan{kPlanSlab, tile_cols}, (hipStream_t)stream, d_status, 1, tile_cols);
+}
+
+int combo_local_sgd_steps_then_gossip_tiled(float* d_dst, const float* d_src, const float* d_grads,
+                                            int32_t tau, float lr, int32_t tile_cols,
+                                            const int32_t* d_peers, const float* d_dataset_sizes,
+                                            int32_t N, int64_t P, int32_t S, int32_t R, void* stream) {
+    const int rc = check_tiled_args(d_dst, d_src, tile_cols, d_peers, N, P, S, R);
+    if (rc != COMBO_OK) return rc;
+    if (tau < 0 || (tau > 0 && (d_grads == nullptr || !aligned16(d_grads)))) return COMBO_EINVAL;
+    const uint64_t bytes = (uint64_t)tiled_elems(N, P, tile_cols) * sizeof(float);
+    if (tau > 0 && (overlaps(d_grads, bytes * (uint64_t)tau, d_src, bytes) ||
+                    overlaps(d_grads, bytes * (uint64_t)tau, d_dst, bytes)))
+        return COMBO_EALIAS;
+    return enqueue_round(d_dst, d_src, tau > 0 ? d_grads : nullptr, lr, tile_cols, d_peers,
+                         d_dataset_sizes, N, P, S, R, Plan{kPlanSlab, tile_cols}, (hipStream_t)stream,
+                         nullptr, tau, tile_cols);
 }
 
 int64_t combo_aggregation_divergence_workspace(int32_t N, int64_t P) {

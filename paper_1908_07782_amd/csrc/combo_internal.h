@@ -29,7 +29,8 @@ struct RoundArgs {
     float inv;               // 1.0f / (float)(R + 1)
     float lr;                // learning rate of the fused local step
     int32_t tau;             // number of fused local steps (gradient slices)
-    int64_t grad_slice;      // elements between consecutive gradient slices (N * ld)
+    int64_t grad_slice;      // elements between consecutive gradient slices
+    int32_t tile_shift;      // 0: row-major [N][ld]; else log2(Wt) of the tiled layout [T][N][Wt]
 };
 
 // launchers (defined in gossip_round.hip / peer_table.hip); return hipGetLastError()
@@ -53,6 +54,12 @@ uint32_t divergence_grid(int32_t N, int64_t P, int strip_cols);
 hipError_t launch_divergence(double* dist2, double* workspace, const float* x, int64_t ld,
                              const float* dsz, int32_t N, int64_t P, int strip_cols, bool vec,
                              hipStream_t st);
+
+// layout conversion kernels (layout.hip)
+hipError_t launch_pack_tiled(float* tiled, const float* rows, int64_t ld, int32_t N, int64_t P,
+                             int tile_cols, hipStream_t st);
+hipError_t launch_unpack_tiled(float* rows, int64_t ld, const float* tiled, int32_t N, int64_t P,
+                               int tile_cols, hipStream_t st);
 
 // Slab kernel: one workgroup stages all N rows of a strip of `strip_cols` columns in
 // LDS.  slab_strip_cols() picks the strip width for N workers (0: does not fit in LDS).

@@ -25,9 +25,11 @@ namespace {
 
 constexpr int kBatch = 4;   // 128-bit loads kept in flight per thread while filling the slab
 
-// Workgroup size of the slab kernel.  Measured on MI355X: 512 threads with about two
-// 128-bit words per thread (a 16 KiB slab) beat 128/256/1024 threads and larger slabs.
-constexpr int kSlabThreads = 512;
+// Workgroup size of the slab kernel: 256 or 512 threads, chosen on the host so that a
+// thread moves about two 128-bit words (measured on MI355X: 8 KiB slabs with 256 threads
+// and 16 KiB slabs with 512 threads beat every other combination of 128..1024 threads
+// and 4..64 KiB slabs).
+constexpr int kSlabThreadsMax = 512;
 
 // every front-buffer element is read once, so the slab fill uses streaming loads
 __device__ __forceinline__ v4f load4_slab(const float* p) {
@@ -36,7 +38,7 @@ __device__ __forceinline__ v4f load4_slab(const float* p) {
 
 // DYNAMIC: Sec. 4.2 semantics (offline rows copied, newcomers aggregated without their own
 // value, unused table slots < 0 skipped, scale by the number of terms).
-template <int RT, bool WEIGHTED, bool FUSED, bool DYNAMIC>
+template <int RT, bool WEIGHTED, bool FUSED, bool DYNAMIC, int kSlabThreads>
 __global__ __launch_bounds__(kSlabThreads) void gossip_slab_kernel(const RoundArgs a, const int W) {
     extern __shared__ v4f lds[];
     const int32_t R = RT >= 0 ? RT : a.R;
@@ -52,6 +54,11 @@ __global__ __launch_bounds__(kSlabThreads) void gossip_slab_kernel(const RoundAr
 
     const int64_t col0 = (int64_t)blockIdx.x * W;
     const int64_t col_end = col0 + W < a.P ? col0 + W : a.P;
+    // where the strip's row chunks live: row-major rows are ld apart and start at col0;
+    // in the tiled layout (tile width == W) the whole slab is one contiguous block
+    const size_t row_stride = a.tile_shift == 0 ? (size_t)a.ld : (size_t)W;
+    const size_t strip_base = a.tile_shift == 0 ? (size_t)col0
+                                                : (size_t)blockIdx.x * (size_t)N * (size_t)W;
     const int32_t s0 = segment_of(col0, a);
     const int64_t seg_end = (s0 == a.S - 1) ? a.P : (int64_t)(s0 + 1) * a.L;
 
@@ -76,7 +83,7 @@ __global__ __launch_bounds__(kSlabThreads) void gossip_slab_kernel(const RoundAr
                 if (idx < total4) {
                     const int row = idx >> w4_shift;
                     const int c4 = idx & (W4 - 1);
-                    off[u] = (size_t)row * (size_t)a.ld + (size_t)col0 + (size_t)c4 * 4;
+                    off[u] = (size_t)row * row_stride + strip_base + (size_t)c4 * 4;
                     x[u] = load4_slab(a.src + off[u]);
                     if (FUSED) g[u] = load4_slab(a.grad + off[u]);
                 }
@@ -159,7 +166,7 @@ __global__ __launch_bounds__(kSlabThreads) void gossip_slab_kernel(const RoundAr
                 }
                 y = div4(acc, den);
             }
-            store4_stream(a.dst + (size_t)w * (size_t)a.ld + (size_t)col0 + (size_t)c4 * 4, y);
+            store4_stream(a.dst + (size_t)w * row_stride + strip_base + (size_t)c4 * 4, y);
         }
     } else {
         // ---- boundary or ragged strip: element by element from global memory --------
@@ -179,12 +186,22 @@ size_t slab_lds_bytes(int32_t N, int32_t R, int W) {
     return (size_t)N * (size_t)W * 4 + (size_t)N * (size_t)R * 4 + (size_t)N * 4 + (size_t)N * 4;
 }
 
+// 256 threads for slabs of up to 768 128-bit words (12 KiB), 512 beyond
+int slab_threads(int32_t N, int W) { return (int64_t)N * (W / 4) <= 768 ? 256 : 512; }
+
 template <int RT>
 hipError_t launch_rt(const RoundArgs& a, int W, uint32_t grid, size_t lds, hipStream_t st) {
     const bool weighted = a.dsz != nullptr, fused = a.grad != nullptr;
-#define COMBO_SLAB_LAUNCH(WT, FU)                                                             \
-    hipLaunchKernelGGL((gossip_slab_kernel<RT, WT, FU, false>), dim3(grid), dim3(kSlabThreads), lds, \
-                       st, a, W)
+    const bool small = slab_threads(a.N, W) == 256;
+#define COMBO_SLAB_LAUNCH(WT, FU)                                                                  \
+    do {                                                                                           \
+        if (small)                                                                                 \
+            hipLaunchKernelGGL((gossip_slab_kernel<RT, WT, FU, false, 256>), dim3(grid), dim3(256),    \
+                               lds, st, a, W);                                                     \
+        else                                                                                       \
+            hipLaunchKernelGGL((gossip_slab_kernel<RT, WT, FU, false, 512>), dim3(grid), dim3(512),    \
+                               lds, st, a, W);                                                     \
+    } while (0)
     if (weighted) {
         if (fused) COMBO_SLAB_LAUNCH(true, true);
         else COMBO_SLAB_LAUNCH(true, false);
@@ -222,12 +239,22 @@ hipError_t launch_round_slab(const RoundArgs& a, int W, hipStream_t st) {
     const uint32_t grid = (uint32_t)strips;
     if (a.status != nullptr) {
         // dynamic workers: run-time replica loop, no fused step
-        if (a.dsz != nullptr)
-            hipLaunchKernelGGL((gossip_slab_kernel<-1, true, false, true>), dim3(grid),
-                               dim3(kSlabThreads), lds, st, a, W);
-        else
-            hipLaunchKernelGGL((gossip_slab_kernel<-1, false, false, true>), dim3(grid),
-                               dim3(kSlabThreads), lds, st, a, W);
+        const bool small = slab_threads(a.N, W) == 256;
+        if (a.dsz != nullptr) {
+            if (small)
+                hipLaunchKernelGGL((gossip_slab_kernel<-1, true, false, true, 256>), dim3(grid),
+                                   dim3(256), lds, st, a, W);
+            else
+                hipLaunchKernelGGL((gossip_slab_kernel<-1, true, false, true, 512>), dim3(grid),
+                                   dim3(512), lds, st, a, W);
+        } else {
+            if (small)
+                hipLaunchKernelGGL((gossip_slab_kernel<-1, false, false, true, 256>), dim3(grid),
+                                   dim3(256), lds, st, a, W);
+            else
+                hipLaunchKernelGGL((gossip_slab_kernel<-1, false, false, true, 512>), dim3(grid),
+                                   dim3(512), lds, st, a, W);
+        }
         return hipGetLastError();
     }
     switch (a.R) {

@@ -63,11 +63,20 @@ __device__ __forceinline__ int32_t segment_of(int64_t e, const RoundArgs& a) {
     return q >= (uint64_t)a.S ? a.S - 1 : (int32_t)q;
 }
 
+// Index of worker `row`'s column e.  Row-major: row*ld + e.  Tiled [T][N][Wt]: tile
+// e / Wt holds Wt consecutive columns of all N workers, worker-major inside the tile.
+__device__ __forceinline__ size_t elem_offset(const RoundArgs& a, int32_t row, int64_t e) {
+    if (a.tile_shift == 0) return (size_t)row * (size_t)a.ld + (size_t)e;
+    const size_t tile = (size_t)e >> a.tile_shift;
+    const size_t in_tile = (size_t)e & (((size_t)1 << a.tile_shift) - 1);
+    return ((tile * (size_t)a.N + (size_t)row) << a.tile_shift) + in_tile;
+}
+
 // pre-aggregation value of worker `row` at column e: the stored parameter, or, when the
 // local steps are fused in, the parameter after the tau SGD steps (in slice order)
 template <bool FUSED>
 __device__ __forceinline__ float served_value(const RoundArgs& a, int32_t row, int64_t e) {
-    const size_t k = (size_t)row * (size_t)a.ld + (size_t)e;
+    const size_t k = elem_offset(a, row, e);
     float x = a.src[k];
     if (FUSED)
         for (int32_t t = 0; t < a.tau; ++t)
@@ -98,7 +107,7 @@ __device__ __forceinline__ void average_element(const RoundArgs& a, int32_t w, i
         }
         out = __fdiv_rn(num, den);
     }
-    a.dst[(size_t)w * (size_t)a.ld + (size_t)e] = out;
+    a.dst[elem_offset(a, w, e)] = out;
 }
 
 // Eq. (3) with dynamic workers (Sec. 4.2) for one element.  status: 0 offline (keeps its
@@ -108,7 +117,7 @@ template <bool WEIGHTED>
 __device__ __forceinline__ void average_element_dynamic(const RoundArgs& a, int32_t w, int64_t e) {
     const int32_t s = segment_of(e, a);
     const int32_t* pl = a.peers + ((size_t)w * (size_t)a.S + (size_t)s) * (size_t)a.R;
-    const float own = a.src[(size_t)w * (size_t)a.ld + (size_t)e];
+    const float own = a.src[elem_offset(a, w, e)];
     const int st = a.status[w];
     int cnt = 0;
     float acc = 0.0f, den = 0.0f;
@@ -121,7 +130,7 @@ __device__ __forceinline__ void average_element_dynamic(const RoundArgs& a, int3
         for (int32_t j = 0; j < a.R; ++j) {
             const int32_t p = pl[j];
             if (p < 0) continue;
-            const float v = a.src[(size_t)p * (size_t)a.ld + (size_t)e];
+            const float v = a.src[elem_offset(a, p, e)];
             if (WEIGHTED) {
                 const float dp = a.dsz[p];
                 const float t = __fmul_rn(dp, v);
@@ -135,7 +144,7 @@ __device__ __forceinline__ void average_element_dynamic(const RoundArgs& a, int3
     }
     float out = own;
     if (cnt > 0) out = WEIGHTED ? __fdiv_rn(acc, den) : __fmul_rn(acc, __fdiv_rn(1.0f, (float)cnt));
-    a.dst[(size_t)w * (size_t)a.ld + (size_t)e] = out;
+    a.dst[elem_offset(a, w, e)] = out;
 }
 
 }  // namespace combo
