@@ -181,8 +181,11 @@ def main():
     ap.add_argument("--replicas", type=int, default=-1,
                     help="override R (0 turns the round into a plain copy of known size: the "
                          "calibration kernel for the HBM byte counters)")
-    ap.add_argument("--layout", choices=["rows", "tiled"], default="rows",
-                    help="arena layout: row-major [N][ld] or tiled [T][N][Wt]")
+    ap.add_argument("--layout", choices=["rows", "tiled"], default="tiled",
+                    help="arena layout: tiled [T][N][Wt] (default, the faster one) or row-major "
+                         "[N][ld]")
+    ap.add_argument("--no-other-layout", action="store_true",
+                    help="skip the short side measurement of the other arena layout")
     ap.add_argument("--tiled-cols", type=int, default=0, help="tile width of the tiled layout")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep-paper", action="store_true",
@@ -220,65 +223,73 @@ def main():
     if args.extras:
         return extras(combo, wl)
 
-    tiled = args.layout == "tiled"
-    Wt = (args.tiled_cols or combo.tiled_cols(wl.N, wl.R)) if tiled else 0
     rows = torch.zeros((wl.N, wl.ld), dtype=torch.float32, device=dev)
     combo.workloads.fill_params(rows, wl)
     X0_host = None
     if not args.no_cpu_baseline:
         X0_host = rows[:, :wl.P].cpu().numpy()
-    if tiled:
-        n = combo.tiled_elems(wl.N, wl.P, Wt)
-        arena = torch.zeros((2, n), dtype=torch.float32, device=dev)
-        combo.pack_tiled(arena[0], rows, wl.N, wl.P, Wt)
-        del rows
-    else:
-        arena = torch.zeros((2, wl.N, wl.ld), dtype=torch.float32, device=dev)
-        arena[0].copy_(rows)
-        del rows
-    grads = None
-    if wl.fused:
-        grads = torch.zeros_like(arena[0])
-        grads.normal_(0.0, wl.grad_std)          # layout-agnostic: i.i.d. values
     peers = torch.empty(max(wl.N * wl.S * wl.R, 1), dtype=torch.int32, device=dev)
     stream = torch.cuda.current_stream()
 
-    state = {"cur": 0, "round": 0}
-
-    def step(ev=None):
-        cur, rnd = state["cur"], state["round"]
-        combo.make_peer_table(peers, wl.N, wl.S, wl.R, wl.hash_seed, rnd, stream=stream)
-        if ev is not None:
-            ev[0].record(stream)
-        if tiled and wl.fused:
-            combo.local_sgd_steps_then_gossip_tiled(arena[1 - cur], arena[cur], grads, 1, wl.lr, Wt,
-                                                    peers, wl.N, wl.P, wl.S, wl.R, stream=stream)
-        elif tiled:
-            combo.segment_gossip_round_tiled(arena[1 - cur], arena[cur], Wt, peers, wl.N, wl.P, wl.S,
-                                             wl.R, stream=stream)
-        elif wl.fused:
-            combo.local_sgd_then_gossip(arena[1 - cur], arena[cur], grads, wl.lr, peers, wl.P, wl.S,
-                                        wl.R, stream=stream)
+    def run_layout(layout, steps, warmup):
+        """Time `steps` steps in one arena layout; returns (wall seconds, kernel ms list, Wt)."""
+        is_tiled = layout == "tiled"
+        wt = (args.tiled_cols or combo.tiled_cols(wl.N, wl.R)) if is_tiled else 0
+        if is_tiled:
+            arena = torch.zeros((2, combo.tiled_elems(wl.N, wl.P, wt)), dtype=torch.float32, device=dev)
+            combo.pack_tiled(arena[0], rows, wl.N, wl.P, wt)
         else:
-            combo.segment_gossip_round(arena[1 - cur], arena[cur], peers, wl.P, wl.S, wl.R,
-                                       stream=stream)
-        if ev is not None:
-            ev[1].record(stream)
-        state["cur"], state["round"] = 1 - cur, rnd + 1
+            arena = torch.zeros((2, wl.N, wl.ld), dtype=torch.float32, device=dev)
+            arena[0].copy_(rows)
+        grads = None
+        if wl.fused:
+            grads = torch.zeros_like(arena[0])
+            grads.normal_(0.0, wl.grad_std)          # layout-agnostic: i.i.d. values
+        state = {"cur": 0, "round": 0}
 
-    for _ in range(args.warmup):
-        step()
-    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-              for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        step(events[k])
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
+        def step(ev=None):
+            cur, rnd = state["cur"], state["round"]
+            combo.make_peer_table(peers, wl.N, wl.S, wl.R, wl.hash_seed, rnd, stream=stream)
+            if ev is not None:
+                ev[0].record(stream)
+            if is_tiled and wl.fused:
+                combo.local_sgd_steps_then_gossip_tiled(arena[1 - cur], arena[cur], grads, 1, wl.lr, wt,
+                                                        peers, wl.N, wl.P, wl.S, wl.R, stream=stream)
+            elif is_tiled:
+                combo.segment_gossip_round_tiled(arena[1 - cur], arena[cur], wt, peers, wl.N, wl.P,
+                                                 wl.S, wl.R, stream=stream)
+            elif wl.fused:
+                combo.local_sgd_then_gossip(arena[1 - cur], arena[cur], grads, wl.lr, peers, wl.P,
+                                            wl.S, wl.R, stream=stream)
+            else:
+                combo.segment_gossip_round(arena[1 - cur], arena[cur], peers, wl.P, wl.S, wl.R,
+                                           stream=stream)
+            if ev is not None:
+                ev[1].record(stream)
+            state["cur"], state["round"] = 1 - cur, rnd + 1
 
-    wall = t1 - t0
-    kern_ms = sorted(a.elapsed_time(b) for a, b in events)
+        for _ in range(warmup):
+            step()
+        events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                  for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(steps):
+            step(events[k])
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        return t1 - t0, sorted(a.elapsed_time(b) for a, b in events), wt
+
+    tiled = args.layout == "tiled"
+    wall, kern_ms, Wt = run_layout(args.layout, args.steps, args.warmup)
+    other = None
+    if not args.no_other_layout:
+        other_name = "rows" if tiled else "tiled"
+        o_wall, o_ms, o_wt = run_layout(other_name, min(args.steps, 20), 3)
+        other = {"layout": other_name, "tiled_cols": o_wt, "rounds_per_s": min(args.steps, 20) / o_wall,
+                 "kernel_ms_avg": sum(o_ms) / len(o_ms)}
+    del rows
+
     kern_avg_ms = sum(kern_ms) / len(kern_ms)
     # (R+1) served values read + 1 written per element; the fused local step adds the
     # read of the gradient (folded into the slab fill) or, in two passes, a read of x and
@@ -329,6 +340,8 @@ def main():
             "kernel_ms_min": kern_ms[0],
         },
     }
+    if other is not None:
+        out["other_layout"] = other
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, X0_host)
         out["cpu_baseline"]["host_cores_visible"] = os.cpu_count()
