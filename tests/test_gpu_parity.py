@@ -436,3 +436,50 @@ def test_multi_step_local_update(combo, ref, tau, mode, N, P, S, R, weighted):
     front = buf[0, :, :P].cpu().numpy()
     assert_params_match(front, Xh if (mode.startswith("fused") or tau == 0) else Xs[:, :P], "front buffer")
     assert bool(torch.isnan(buf[:, :, P:]).all())
+
+
+def test_rounds_can_be_captured_in_a_hip_graph(combo, ref):
+    """The library neither allocates nor synchronises nor memsets, so a caller may capture
+    peer-table + round launches in a HIP graph.  The graph (two rounds, A -> B -> A) is
+    replayed several times with eager work and synchronisations in between; every replay
+    must equal the same calls made eagerly."""
+    N, P, S, R = 8, 50_003, 5, 3
+    ld = combo.workloads.row_pitch(P)
+    Xh = np.random.default_rng(7).normal(0, 0.05, (N, P)).astype(np.float32)
+    A = torch.zeros((N, ld), dtype=torch.float32, device="cuda")
+    A[:, :P] = torch.from_numpy(Xh).cuda()
+    B = torch.zeros_like(A)
+    peers = torch.empty(N * S * R, dtype=torch.int32, device="cuda")
+    eA, eB, ep = A.clone(), B.clone(), peers.clone()
+
+    def two_rounds(a, b, p, stream):
+        combo.make_peer_table(p, N, S, R, 3, 0, stream=stream)
+        combo.segment_gossip_round(b, a, p, P, S, R, stream=stream)
+        combo.make_peer_table(p, N, S, R, 3, 1, stream=stream)
+        combo.segment_gossip_round(a, b, p, P, S, R, stream=stream)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        two_rounds(A, B, peers, side)                 # warm-up on the capture stream
+    side.synchronize()
+    A.copy_(eA)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        two_rounds(A, B, peers, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    A.copy_(eA)                                       # capture does not execute; start clean
+    for replay in range(4):
+        graph.replay()
+        two_rounds(eA, eB, ep, torch.cuda.current_stream())
+        junk = torch.randn(1000, device="cuda").sum()   # unrelated eager work in between
+        torch.cuda.synchronize()
+        assert torch.equal(A.view(torch.int32), eA.view(torch.int32)), replay
+        assert torch.equal(B.view(torch.int32), eB.view(torch.int32)), replay
+        assert float(junk) == float(junk)
+    # and the eager chain is the oracle's: 8 rounds alternating tables of round 0 and 1
+    X = Xh
+    for k in range(8):
+        X = ref.gossip_round(X, ref.make_peer_table(N, S, R, 3, k % 2), P, S, R)
+    assert_params_match(eA[:, :P].cpu().numpy(), X, "graph chain")

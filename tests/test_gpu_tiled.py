@@ -204,3 +204,60 @@ def test_full_size_workloads_tiled_on_sampled_windows(combo, ref, name):
     assert not bool(torch.isnan(last[T - 1, :, :tail]).any())
     if tail < Wt:      # half 1 started as NaN everywhere: its padding was never written
         assert bool(torch.isnan(arena[1].view(T, wl.N, Wt)[T - 1, :, tail:]).all())
+
+
+@pytest.mark.parametrize("layout", ["rows", "tiled"])
+def test_more_than_two_to_the_32_columns(combo, ref, layout):
+    """P > 2^32: column indices, segment lookup and offsets need 64 bits (a 17 GB row).
+    N=2, S=3, R=1, two rounds, checked on windows at the row start and end, at both
+    segment boundaries and across column 2^32."""
+    from paper_1908_07782_amd.workloads import Workload
+    import tests.test_gpu_parity as tp
+    P = 2**32 + 4099
+    wl = Workload("wide", N=2, P=P, S=3, R=1, rounds=2, dist="normal", scale=0.05)
+    L = P // 3
+    wins = [(0, 3000), (P - 3000, 3000), (L - 1500, 3000), (2 * L - 1500, 3000), (2**32 - 1500, 3000),
+            (2**31 - 1500, 3000)]
+    peers = torch.empty(wl.N * wl.S * wl.R, dtype=torch.int32, device="cuda")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(5)
+    if layout == "rows":
+        arena = torch.empty((2, wl.N, wl.ld), dtype=torch.float32, device="cuda")
+        arena[1].fill_(float("nan"))
+        for w in range(wl.N):
+            arena[0, w].normal_(0.0, wl.scale, generator=g)
+
+        def window(buf, c0, nc):
+            return buf[:, c0:c0 + nc].contiguous().cpu().numpy()
+    else:
+        Wt = combo.tiled_cols(wl.N, wl.R)
+        n = combo.tiled_elems(wl.N, P, Wt)
+        T = n // (wl.N * Wt)
+        arena = torch.empty((2, n), dtype=torch.float32, device="cuda")
+        arena[1].fill_(float("nan"))
+        half = n // 2 // 4 * 4
+        arena[0, :half].normal_(0.0, wl.scale, generator=g)
+        arena[0, half:].normal_(0.0, wl.scale, generator=g)
+
+        def window(buf, c0, nc):
+            t_lo, t_hi = c0 // Wt, (c0 + nc - 1) // Wt + 1
+            blk = buf.view(T, wl.N, Wt)[t_lo:t_hi].permute(1, 0, 2).reshape(wl.N, -1)
+            return blk[:, c0 - t_lo * Wt:c0 - t_lo * Wt + nc].contiguous().cpu().numpy()
+    X0 = {w: window(arena[0], *w) for w in wins}
+    cur = 0
+    for rnd in range(wl.rounds):
+        combo.make_peer_table(peers, wl.N, wl.S, wl.R, wl.hash_seed, rnd)
+        if layout == "rows":
+            combo.segment_gossip_round(arena[1 - cur], arena[cur], peers, P, wl.S, wl.R)
+        else:
+            combo.segment_gossip_round_tiled(arena[1 - cur], arena[cur], Wt, peers, wl.N, P, wl.S, wl.R)
+        cur = 1 - cur
+    torch.cuda.synchronize()
+    for w in wins:
+        want = tp.oracle_rounds_on_window(ref, wl, X0[w], w[0], wl.rounds)
+        got = window(arena[cur], *w)
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), (layout, w)
+    # after one round the other half was written everywhere inside the rows
+    if layout == "rows":
+        assert not bool(torch.isnan(arena[1, :, :P]).any())
+        assert bool(torch.isnan(arena[1, :, P:]).all())
