@@ -141,6 +141,13 @@ def extras(combo, wl):
     emit("combo_aggregation_divergence", time_kernel(
         lambda: combo.aggregation_divergence(d2, arena[0], P, ws, stream=stream), stream),
         4 * N * P, note="bytes = one read of every element")
+    Wt = combo.tiled_cols(N, R)
+    tiled = torch.zeros(combo.tiled_elems(N, P, Wt), dtype=torch.float32, device="cuda")
+    combo.pack_tiled(tiled, arena[0], N, P, Wt)
+    emit("combo_aggregation_divergence_tiled", time_kernel(
+        lambda: combo.aggregation_divergence_tiled(d2, tiled, Wt, N, P, ws, stream=stream), stream),
+        4 * N * P, note="bytes = one read of every element", tiled_cols=Wt)
+    del tiled
     # dynamic round with every tenth worker offline and one newcomer
     st = torch.ones(N, dtype=torch.uint8)
     st[::10] = 0

@@ -244,14 +244,21 @@ int combo_local_sgd_steps_then_gossip_tiled(float* d_dst, const float* d_src, co
  *   d_workspace  scratch, device, 8-byte aligned, at least
  *                combo_aggregation_divergence_workspace(N, P) bytes; contents irrelevant
  *                before and after the call
+ * combo_aggregation_divergence_tiled reads a tiled matrix [T][N][tile_cols] instead
+ *.
  * Errors: COMBO_EINVAL for bad sizes, NULL pointers, a workspace that is too small or
- * misaligned; COMBO_ERANGE when N rows of a 64-column strip do not fit in LDS (N > ~230).
- * combo_aggregation_divergence_workspace returns the byte count, or a negative status.
+ * misaligned; COMBO_ERANGE for N > 256, or when N rows of a tile exceed the kernel's
+ * register slots (N * tile_cols > 16384).
+ * combo_aggregation_divergence_workspace returns the byte count (4096*N*8), or a negative
+ * status.
  */
 int64_t combo_aggregation_divergence_workspace(int32_t N, int64_t P);
 int combo_aggregation_divergence(double* d_dist2, const float* d_x, int64_t ld,
                                  const float* d_dataset_sizes, int32_t N, int64_t P,
                                  void* d_workspace, int64_t workspace_bytes, void* stream);
+int combo_aggregation_divergence_tiled(double* d_dist2, const float* d_x, int32_t tile_cols,
+                                       const float* d_dataset_sizes, int32_t N, int64_t P,
+                                       void* d_workspace, int64_t workspace_bytes, void* stream);
 
 /*
  * Performance knobs (process-global, host side only; results never depend on them).

@@ -11,6 +11,7 @@ from .binding import (ComboError, get_tune, lib, local_sgd_then_gossip, make_pee
                       segment_gossip_round_dynamic, aggregation_divergence,
                       aggregation_divergence_workspace, local_sgd_steps_then_gossip,
                       tiled_cols, tiled_elems, pack_tiled, unpack_tiled,
-                      segment_gossip_round_tiled, local_sgd_steps_then_gossip_tiled,  # noqa: F401
+                      segment_gossip_round_tiled, local_sgd_steps_then_gossip_tiled,
+                      aggregation_divergence_tiled,  # noqa: F401
                       segment_gossip_round, strerror, tune, TUNE_FUSED_MODE, TUNE_TILE_COLS,
                       TUNE_XCD_SWIZZLE, TUNE_KERNEL, TUNE_SLAB_COLS, LIB_PATH)

@@ -13,7 +13,7 @@ TUNE_FUSED_MODE = 2
 TUNE_KERNEL = 3
 TUNE_SLAB_COLS = 4
 
-EXPORTS = ("combo_tiled_cols", "combo_tiled_elems", "combo_pack_tiled", "combo_unpack_tiled",
+EXPORTS = ("combo_aggregation_divergence_tiled", "combo_tiled_cols", "combo_tiled_elems", "combo_pack_tiled", "combo_unpack_tiled",
            "combo_segment_gossip_round_tiled", "combo_local_sgd_steps_then_gossip_tiled",
            "combo_local_sgd_steps_then_gossip", "combo_aggregation_divergence", "combo_aggregation_divergence_workspace",
            "combo_make_peer_table_dynamic", "combo_segment_gossip_round_dynamic",
@@ -73,6 +73,8 @@ def lib():
         L.combo_local_sgd_steps_then_gossip_tiled.argtypes = [vp, vp, vp, i32, f32, i32, vp, vp, i32,
                                                               i64, i32, i32, vp]
         L.combo_local_sgd_steps_then_gossip_tiled.restype = ctypes.c_int
+        L.combo_aggregation_divergence_tiled.argtypes = [vp, vp, i32, vp, i32, i64, vp, i64, vp]
+        L.combo_aggregation_divergence_tiled.restype = ctypes.c_int
         L.combo_tune.argtypes = [ctypes.c_int, ctypes.c_int]
         L.combo_tune.restype = ctypes.c_int
         L.combo_get_tune.argtypes = [ctypes.c_int]
@@ -339,3 +341,17 @@ def local_sgd_steps_then_gossip_tiled(dst, src, grads, tau, lr, tile_cols, peers
     if rc:
         raise ComboError(rc, "combo_local_sgd_steps_then_gossip_tiled")
     return dst
+
+
+def aggregation_divergence_tiled(dist2, x, tile_cols, N, P, workspace, dataset_sizes=None, stream=None):
+    """combo_aggregation_divergence_tiled: x is a flat tiled buffer [T][N][tile_cols]."""
+    if dist2.numel() < N or not dist2.is_contiguous():
+        raise ValueError("dist2: need a contiguous float64 device tensor with N entries")
+    rc = lib().combo_aggregation_divergence_tiled(
+        _dev_ptr(dist2, torch.float64, "dist2"), _flat(x, tiled_elems(N, P, tile_cols), "x"), tile_cols,
+        _dev_ptr(dataset_sizes, torch.float32, "dataset_sizes", optional=True), N, P,
+        ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
+        _stream_ptr(stream))
+    if rc:
+        raise ComboError(rc, "combo_aggregation_divergence_tiled")
+    return dist2

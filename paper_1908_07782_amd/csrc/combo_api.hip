@@ -301,9 +301,8 @@ int combo_local_sgd_steps_then_gossip_tiled(float* d_dst, const float* d_src, co
 
 int64_t combo_aggregation_divergence_workspace(int32_t N, int64_t P) {
     if (N < 1 || P < 1) return COMBO_EINVAL;
-    const int W = combo::divergence_strip_cols(N);
-    if (W == 0) return COMBO_ERANGE;
-    return (int64_t)combo::divergence_grid(N, P, W) * (int64_t)N * (int64_t)sizeof(double);
+    if (combo::divergence_strip_cols(N) == 0) return COMBO_ERANGE;
+    return (int64_t)4096 * (int64_t)N * (int64_t)sizeof(double);   // one partial per workgroup and row
 }
 
 int combo_aggregation_divergence(double* d_dist2, const float* d_x, int64_t ld,
@@ -317,7 +316,27 @@ int combo_aggregation_divergence(double* d_dist2, const float* d_x, int64_t ld,
     const int W = combo::divergence_strip_cols(N);
     const bool vec = aligned16(d_x) && (ld % 4 == 0);
     const hipError_t e = combo::launch_divergence(d_dist2, (double*)d_workspace, d_x, ld,
-                                                  d_dataset_sizes, N, P, W, vec, (hipStream_t)stream);
+                                                  d_dataset_sizes, N, P, W, vec, 0,
+                                                  (hipStream_t)stream);
+    return e == hipSuccess ? COMBO_OK : COMBO_EHIP;
+}
+
+int combo_aggregation_divergence_tiled(double* d_dist2, const float* d_x, int32_t tile_cols,
+                                       const float* d_dataset_sizes, int32_t N, int64_t P,
+                                       void* d_workspace, int64_t workspace_bytes, void* stream) {
+    if (N < 1 || P < 1 || !tile_cols_ok(tile_cols) || d_dist2 == nullptr || d_x == nullptr ||
+        !aligned16(d_x))
+        return COMBO_EINVAL;
+    int W = combo::divergence_strip_cols(N);         // a strip spans W / tile_cols whole tiles
+    if (W < tile_cols) W = tile_cols;
+    if (!combo::divergence_width_ok(N, W)) return COMBO_ERANGE;
+    const int64_t need = combo_aggregation_divergence_workspace(N, P);
+    if (need < 0) return (int)need;
+    if (d_workspace == nullptr || workspace_bytes < need || ((uintptr_t)d_workspace & 7u) != 0)
+        return COMBO_EINVAL;
+    const hipError_t e = combo::launch_divergence(d_dist2, (double*)d_workspace, d_x, tile_cols,
+                                                  d_dataset_sizes, N, P, W, true, tile_cols,
+                                                  (hipStream_t)stream);
     return e == hipSuccess ? COMBO_OK : COMBO_EHIP;
 }
 

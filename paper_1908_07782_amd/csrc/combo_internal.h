@@ -50,10 +50,10 @@ hipError_t launch_peer_in_degree(int32_t* deg, const int32_t* peers, int32_t N, 
 
 // Aggregation divergence (divergence.hip)
 int divergence_strip_cols(int32_t N);
-uint32_t divergence_grid(int32_t N, int64_t P, int strip_cols);
+bool divergence_width_ok(int32_t N, int strip_cols);
 hipError_t launch_divergence(double* dist2, double* workspace, const float* x, int64_t ld,
                              const float* dsz, int32_t N, int64_t P, int strip_cols, bool vec,
-                             hipStream_t st);
+                             int arena_tile, hipStream_t st);
 
 // layout conversion kernels (layout.hip)
 hipError_t launch_pack_tiled(float* tiled, const float* rows, int64_t ld, int32_t N, int64_t P,

@@ -3,141 +3,190 @@
 // workers (the dataset-size weighted mean; the plain mean for equal sizes).
 //
 // Read-only streaming pass, HBM bound (4 bytes per element).  A persistent workgroup
-// walks over column strips.  For each strip every thread loads its 128-bit words of the
-// N x W slab (the same (row, column-in-strip) slots for every strip), keeps them in
-// registers and also parks them in LDS; the W column means are then formed in binary64
-// from LDS (each of the 512/W thread groups sums a share of the workers, the shares are
-// added in group order); finally every thread squares the differences of its own
-// register values against the means and adds them to a private binary64 accumulator per
-// slot.  A slot always belongs to the same worker row, so nothing is reduced per strip:
-// only at the end of the kernel are the slots of a row added (in slot order) and the
-// workgroup's N partial sums written to a caller-supplied workspace.  A second tiny
-// kernel adds the partials of each row with a fixed tree.  No floating-point atomics, so the
-// result is reproducible bit for bit.
+// walks over column strips of W columns.  Every thread owns the same (row, 4-column group)
+// slots in every strip: slot k of thread t is row k*(threads/W4) + t/W4, columns
+// 4*(t mod W4)..+3 (W4 = W/4).  Per strip it loads its 128-bit words into registers, adds
+// its own rows' (weighted) values in binary64, adds the lanes of its wavefront that hold
+// the same column group with a fixed xor-shuffle tree, and the wavefronts exchange their
+// four column sums through a small LDS buffer; after ONE barrier every thread adds the
+// wavefronts' sums in wavefront order, divides, and squares the differences of its
+// register values against the means into one binary64 accumulator per slot.  The LDS
+// exchange buffer is double-buffered, so one barrier per strip suffices and no parameter
+// data is ever staged in LDS.  A slot always
+// belongs to the same worker row, so nothing is reduced per strip: at the end of the
+// kernel the slots of a row are added in slot order and the workgroup's N partial sums
+// go to a caller-supplied workspace; a second tiny kernel adds the partials of each row
+// with a fixed tree.  No floating-point atomics: the result is reproducible bit for bit.
+//
+// Layouts: row-major [N][ld] and tiled [T][N][Wt] (a strip then spans W/Wt whole tiles).
 #include "combo_internal.h"
 #include "round_device.h"
 
 namespace combo {
 namespace {
 
-// Workgroup size: 256 threads (8 KiB slabs, eight workgroups per compute unit) measured
-// 20-25 % faster than 512; 512 is kept for many workers, whose slab needs the extra
-// register slots.
 constexpr int kDivThreadsMax = 512;
+constexpr int kDivSlots = 8;   // 128-bit words per thread and strip; filling all eight
+                               // (measured: 2 words 2.8, 4 words 4.7, 8 words 6.0 TB/s) keeps
+                               // enough loads in flight for the persistent workgroups
 
-constexpr int kDivSlots = 8;   // 128-bit words per thread: slabs up to 64 KiB
+struct DivArgs {
+    double* partial;
+    const float* x;
+    const float* dsz;
+    int64_t ld;
+    int64_t P;
+    int32_t N;
+    int32_t W;            // strip width (power of two, 64..512)
+    uint32_t nstrips;
+    int32_t vec;          // 16-byte aligned with ld % 4 == 0: 128-bit loads allowed
+    int32_t tile_shift;   // 0: row-major [N][ld]; else log2(Wt) of a tiled arena [T][N][Wt], W % Wt == 0
+};
 
 template <bool WEIGHTED, int kDivThreads>
-__global__ __launch_bounds__(kDivThreads) void divergence_partial_kernel(
-    double* __restrict__ partial, const float* __restrict__ x, int64_t ld,
-    const float* __restrict__ dsz, int32_t N, int64_t P, int W, uint32_t nstrips, int vec) {
+__global__ __launch_bounds__(kDivThreads) void divergence_partial_kernel(const DivArgs a) {
     extern __shared__ double lds64[];
+    const int N = a.N, W = a.W;
     const int W4 = W >> 2;
     const int w4_shift = 31 - __clz(W4);
     const int total4 = N * W4;
-    v4f* slab = reinterpret_cast<v4f*>(lds64);        // [N][W4]
-    double* mean = lds64 + 2 * total4;                // [W]
-    double* share = mean + W;                         // [kDivThreads]: partial column sums / fold
-    float* lds_d = reinterpret_cast<float*>(share + kDivThreads);   // [N]
+    const int groups = kDivThreads >> w4_shift;       // threads sharing one column group
+    double* share = lds64;                            // [2][kDivThreads][4]
+    double* fold = share + 2 * kDivThreads * 4;       // [kDivThreads] end-of-kernel fold
+    float* lds_d = reinterpret_cast<float*>(fold + kDivThreads);   // [N]
     const int t = (int)threadIdx.x;
+    const int my_c4 = t & (W4 - 1);
+    const int my_row0 = t >> w4_shift;
 
     if (WEIGHTED)
-        for (int i = t; i < N; i += kDivThreads) lds_d[i] = dsz[i];
+        for (int i = t; i < N; i += kDivThreads) lds_d[i] = a.dsz[i];
     __syncthreads();
     double den = 0.0;
     if (WEIGHTED) { for (int w = 0; w < N; ++w) den += (double)lds_d[w]; }
     else den = (double)N;
+    const double inv_den = 1.0 / den;                 // one division per thread, not four per strip
 
-    const int groups = kDivThreads / W;              // thread groups sharing the column sums
-    const int my_group = t / W, my_col = t - my_group * W;
-    const float* slab_f = reinterpret_cast<const float*>(slab);
-
+    double wt[kDivSlots];                             // dataset size of each slot's row
+#pragma unroll
+    for (int k = 0; k < kDivSlots; ++k) {
+        const int row = k * groups + my_row0;
+        wt[k] = (WEIGHTED && row < N) ? (double)lds_d[row] : 1.0;
+    }
     double acc[kDivSlots];
 #pragma unroll
     for (int k = 0; k < kDivSlots; ++k) acc[k] = 0.0;
 
-    // loads of one strip into registers (zero beyond the ragged end of the row)
-    auto load_strip = [&](uint32_t strip, v4f (&dst)[kDivSlots]) {
+    int buf = 0;
+    for (uint32_t strip = blockIdx.x; strip < a.nstrips; strip += gridDim.x) {
         const int64_t col0 = (int64_t)strip * W;
-        const int width = (int)(col0 + W <= P ? W : P - col0);
-        const bool fast = vec && width == W;
+        const int width = (int)(col0 + W <= a.P ? W : a.P - col0);
+        const bool fast = a.vec && width == W;
+        v4f v[kDivSlots];
 #pragma unroll
         for (int k = 0; k < kDivSlots; ++k) {
-            const int idx = k * kDivThreads + t;
-            if (idx < total4) {
-                const int row = idx >> w4_shift;
-                const int c = (idx & (W4 - 1)) * 4;
-                const float* p = x + (size_t)row * (size_t)ld + (size_t)col0 + (size_t)c;
+            const int row = k * groups + my_row0;
+            if (k * kDivThreads < total4 && row < N) {
+                const int c = my_c4 * 4;
+                const float* p;
+                if (a.tile_shift == 0) {
+                    p = a.x + (size_t)row * (size_t)a.ld + (size_t)col0 + (size_t)c;
+                } else {                              // the four columns lie in one tile
+                    const size_t col = (size_t)col0 + (size_t)c;
+                    const size_t tile = col >> a.tile_shift;
+                    const size_t in_tile = col & (((size_t)1 << a.tile_shift) - 1);
+                    p = a.x + ((tile * (size_t)N + (size_t)row) << a.tile_shift) + in_tile;
+                }
                 if (fast) {
-                    dst[k] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
-                } else {
-                    dst[k].x = c + 0 < width ? p[0] : 0.0f;
-                    dst[k].y = c + 1 < width ? p[1] : 0.0f;
-                    dst[k].z = c + 2 < width ? p[2] : 0.0f;
-                    dst[k].w = c + 3 < width ? p[3] : 0.0f;
+                    v[k] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+                } else {                              // ragged end or unaligned: zero beyond the row
+                    v[k].x = c + 0 < width ? p[0] : 0.0f;
+                    v[k].y = c + 1 < width ? p[1] : 0.0f;
+                    v[k].z = c + 2 < width ? p[2] : 0.0f;
+                    v[k].w = c + 3 < width ? p[3] : 0.0f;
                 }
             }
         }
-    };
-
-    // (Prefetching the next strip into a second register set while this one is reduced was
-    // measured slower than letting the four resident workgroups of a compute unit overlap.)
-    for (uint32_t strip = blockIdx.x; strip < nstrips; strip += gridDim.x) {
-        v4f v[kDivSlots];
-        load_strip(strip, v);
+        // this thread's share of the four column sums
+        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
 #pragma unroll
         for (int k = 0; k < kDivSlots; ++k) {
-            const int idx = k * kDivThreads + t;
-            if (idx < total4) slab[idx] = v[k];
+            const int row = k * groups + my_row0;
+            if (k * kDivThreads < total4 && row < N) {
+                s0 += wt[k] * (double)v[k].x;
+                s1 += wt[k] * (double)v[k].y;
+                s2 += wt[k] * (double)v[k].z;
+                s3 += wt[k] * (double)v[k].w;
+            }
+        }
+        // lanes of one wavefront that share a column group: fixed xor tree
+        for (int off = W4; off < 64; off <<= 1) {
+            s0 += __shfl_xor(s0, off, 64);
+            s1 += __shfl_xor(s1, off, 64);
+            s2 += __shfl_xor(s2, off, 64);
+            s3 += __shfl_xor(s3, off, 64);
+        }
+        // wavefronts exchange their sums through LDS: share[buf][wave][lane][4]
+        double* sh = share + (size_t)buf * kDivThreads * 4;
+        const int lane = t & 63, wave = t >> 6;
+        if (lane < W4) {
+            double* q = sh + (size_t)(wave * 64 + lane) * 4;
+            q[0] = s0;
+            q[1] = s1;
+            q[2] = s2;
+            q[3] = s3;
         }
         __syncthreads();
-        {   // share of the column sum: workers my_group, my_group + groups, ...
-            double num = 0.0;
-            for (int w = my_group; w < N; w += groups)
-                num += (WEIGHTED ? (double)lds_d[w] : 1.0) * (double)slab_f[w * W + my_col];
-            share[t] = num;
+        double m0 = 0.0, m1 = 0.0, m2 = 0.0, m3 = 0.0;
+        {
+            const int my_hi = my_c4 & ~63;            // which 64-group block of columns (W4 > 64)
+#pragma unroll
+            for (int wv = 0; wv < kDivThreads / 64; ++wv) {
+                if (((wv << 6) & (W4 - 1)) == my_hi) {
+                    const double* q = sh + (size_t)(wv * 64 + (my_c4 & 63)) * 4;
+                    m0 += q[0];
+                    m1 += q[1];
+                    m2 += q[2];
+                    m3 += q[3];
+                }
+            }
+            m0 *= inv_den;
+            m1 *= inv_den;
+            m2 *= inv_den;
+            m3 *= inv_den;
         }
-        __syncthreads();
-        if (t < W) {
-            double num = 0.0;
-            for (int gidx = 0; gidx < groups; ++gidx) num += share[gidx * W + t];
-            mean[t] = num / den;
-        }
-        __syncthreads();
 #pragma unroll
         for (int k = 0; k < kDivSlots; ++k) {
-            const int idx = k * kDivThreads + t;
-            if (idx < total4) {
-                const int c = (idx & (W4 - 1)) * 4;
-                const double d0 = (double)v[k].x - mean[c + 0];
-                const double d1 = (double)v[k].y - mean[c + 1];
-                const double d2 = (double)v[k].z - mean[c + 2];
-                const double d3 = (double)v[k].w - mean[c + 3];
+            const int row = k * groups + my_row0;
+            if (k * kDivThreads < total4 && row < N) {
+                const int c = my_c4 * 4;
+                // columns beyond the ragged end hold zeros and a zero mean: no contribution
+                const double d0 = (double)v[k].x - m0;
+                const double d1 = (double)v[k].y - m1;
+                const double d2 = (double)v[k].z - m2;
+                const double d3 = (double)v[k].w - m3;
+                (void)c;
                 acc[k] += (d0 * d0 + d1 * d1) + (d2 * d2 + d3 * d3);
             }
         }
-        // no barrier needed here: the next strip writes slab (last read two barriers ago)
-        // and share (last read one barrier ago); mean is rewritten three barriers later
+        buf ^= 1;     // the other exchange buffer is free: its readers have passed this strip's barrier
     }
 
-    // fold: slot k of thread t belongs to row (k*512 + t) >> w4_shift; add a row's slots in
-    // slot order, one pass per k
+    // fold: slot k of thread t belongs to row k*groups + t/W4; add a row's threads in
+    // thread order, slot by slot
     double row_sum = 0.0;
 #pragma unroll
     for (int k = 0; k < kDivSlots; ++k) {
         if (k * kDivThreads < total4) {               // uniform
             __syncthreads();
-            share[t] = acc[k];
+            fold[t] = acc[k];
             __syncthreads();
-            if (t < N) {
-                const int lo = t * W4 - k * kDivThreads;          // first slot of row t in this pass
-                const int first = lo < 0 ? 0 : lo;
-                const int last = lo + W4 < kDivThreads ? lo + W4 : kDivThreads;
-                for (int i = first; i < last; ++i) row_sum += share[i];
-            }
+            // row r is served in this pass by threads [ (r - k*groups)*W4, +W4 ) if in range
+            const int g = t - k * groups;             // candidate: thread t folds row t
+            if (t < N && g >= 0 && g < groups)
+                for (int i = 0; i < W4; ++i) row_sum += fold[g * W4 + i];
         }
     }
-    if (t < N) partial[(size_t)t * (size_t)gridDim.x + (size_t)blockIdx.x] = row_sum;   // [N][grid]
+    if (t < N) a.partial[(size_t)t * (size_t)gridDim.x + (size_t)blockIdx.x] = row_sum;   // [N][grid]
 }
 
 // dist2[r] = sum over workgroups of partial[r][b]: one workgroup per worker row, each
@@ -160,44 +209,76 @@ __global__ __launch_bounds__(256) void divergence_reduce_kernel(double* __restri
 }
 
 size_t divergence_lds_bytes(int32_t N, int W, int threads) {
-    // slab, column means, share/fold buffer, dataset sizes
-    return (size_t)N * (size_t)W * 4 + (size_t)W * 8 + (size_t)threads * 8 + (size_t)N * 4;
+    // two exchange buffers, fold buffer, dataset sizes
+    (void)W;
+    return (size_t)2 * threads * 4 * 8 + (size_t)threads * 8 + (size_t)N * 4;
 }
-
-// 256 threads when N rows of a 64-column strip fit in their register slots (N <= 128)
-int divergence_threads(int32_t N) { return (int64_t)N * 16 <= 256 * kDivSlots ? 256 : 512; }
 
 }  // namespace
 
-// strip width for the divergence pass, 0 if N rows of 64 columns do not fit in LDS
-int divergence_strip_cols(int32_t N) {
-    if (N > kDivThreadsMax) return 0;                // one fold thread per worker
-    const int threads = divergence_threads(N);
-    for (int W = 512; W >= 64; W >>= 1)
-        if ((size_t)N * (size_t)W * 4 <= (size_t)threads * 32 && W <= threads &&
-            divergence_lds_bytes(N, W, threads) <= 64 * 1024)
-            return W;
-    return ((int64_t)N * 16 <= (int64_t)threads * kDivSlots &&
-            divergence_lds_bytes(N, 64, threads) <= 64 * 1024) ? 64 : 0;
+// 256 threads while N rows of the strip fit in their register slots, else 512
+int divergence_threads(int32_t N, int W) {
+    return (int64_t)N * (W / 4) <= 256 * kDivSlots ? 256 : 512;
 }
 
-uint32_t divergence_grid(int32_t N, int64_t P, int W) {
-    const uint64_t strips = ((uint64_t)P + (uint64_t)W - 1) / (uint64_t)W;
-    const uint64_t cap = divergence_threads(N) == 256 ? 4096 : 2048;   // resident workgroups x 2
-    return (uint32_t)(strips < cap ? strips : cap);
+// strip width: the widest one whose N rows fill at most eight 128-bit words per thread of
+// a 256-thread workgroup (0: N too large)
+int divergence_strip_cols(int32_t N) {
+    if (N > kDivThreadsMax) return 0;                // one fold thread per worker
+    for (int W = 512; W >= 64; W >>= 1)
+        if ((int64_t)N * (W / 4) <= kDivSlots * 256) return W;
+    return (int64_t)N * 16 <= (int64_t)kDivThreadsMax * kDivSlots ? 64 : 0;
+}
+
+// can a strip of W columns (e.g. the tile width of a tiled arena) be handled at all
+bool divergence_width_ok(int32_t N, int W) {
+    return N <= kDivThreadsMax && W >= 64 && W <= 512 && (W & (W - 1)) == 0 &&
+           (int64_t)N * (W / 4) <= (int64_t)divergence_threads(N, W) * kDivSlots;
 }
 
 hipError_t launch_divergence(double* dist2, double* workspace, const float* x, int64_t ld,
-                             const float* dsz, int32_t N, int64_t P, int W, bool vec,
+                             const float* dsz, int32_t N, int64_t P, int W, bool vec, int arena_tile,
                              hipStream_t st) {
     const uint64_t strips = ((uint64_t)P + (uint64_t)W - 1) / (uint64_t)W;
     if (strips > 0xFFFFFFFFull) return hipErrorInvalidValue;
-    const uint32_t grid = divergence_grid(N, P, W);
-    const int threads = divergence_threads(N);
+    const int threads = divergence_threads(N, W);
     const size_t lds = divergence_lds_bytes(N, W, threads);
-#define COMBO_DIV_LAUNCH(WT, TH)                                                                  \
-    hipLaunchKernelGGL((divergence_partial_kernel<WT, TH>), dim3(grid), dim3(TH), lds, st, workspace, \
-                       x, ld, dsz, N, P, W, (uint32_t)strips, vec ? 1 : 0)
+    // persistent grid: exactly the workgroups that are resident at once (no tail round)
+    static int resident[2][2] = {{0, 0}, {0, 0}};   // [weighted][512 threads]
+    int& res = resident[dsz != nullptr][threads == 512];
+    if (res == 0) {
+        int per_cu = 0, dev = 0, cus = 0;
+        hipError_t qe;
+        if (dsz != nullptr)
+            qe = threads == 256
+                     ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, divergence_partial_kernel<true, 256>, 256, lds)
+                     : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, divergence_partial_kernel<true, 512>, 512, lds);
+        else
+            qe = threads == 256
+                     ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, divergence_partial_kernel<false, 256>, 256, lds)
+                     : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, divergence_partial_kernel<false, 512>, 512, lds);
+        if (qe != hipSuccess || hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            return hipErrorUnknown;
+        res = per_cu * cus;
+        if (res < 1) res = 256;
+        if (res > 4096) res = 4096;                  // the workspace holds 4096 partials per row
+    }
+    const uint32_t grid = (uint32_t)(strips < (uint64_t)res ? strips : (uint64_t)res);
+    DivArgs a;
+    a.partial = workspace;
+    a.x = x;
+    a.dsz = dsz;
+    a.ld = ld;
+    a.P = P;
+    a.N = N;
+    a.W = W;
+    a.nstrips = (uint32_t)strips;
+    a.vec = vec ? 1 : 0;
+    a.tile_shift = 0;
+    while (arena_tile && (1 << a.tile_shift) < arena_tile) ++a.tile_shift;
+#define COMBO_DIV_LAUNCH(WT, TH) \
+    hipLaunchKernelGGL((divergence_partial_kernel<WT, TH>), dim3(grid), dim3(TH), lds, st, a)
     if (dsz != nullptr) {
         if (threads == 256) COMBO_DIV_LAUNCH(true, 256);
         else COMBO_DIV_LAUNCH(true, 512);

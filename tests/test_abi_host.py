@@ -96,7 +96,7 @@ def test_divergence_argument_errors(L):
     assert ws(0, 10) == EINVAL and ws(4, 0) == EINVAL and ws(600, 1000) == ERANGE
     need = ws(32, 11_689_512)
     assert need == 4096 * 32 * 8
-    assert ws(4, 100) == 1 * 4 * 8                       # N=4: one 512-column strip
+    assert ws(4, 100) == 4096 * 4 * 8
     f = L.combo_aggregation_divergence
     assert f(None, FAKE_B, 1024, None, 4, 1000, FAKE_C, 10**6, None) == EINVAL
     assert f(FAKE_A, FAKE_B, 999, None, 4, 1000, FAKE_C, 10**6, None) == EINVAL

@@ -31,7 +31,7 @@ def gpu_divergence(combo, x, P, d=None):
 
 
 @pytest.mark.parametrize("N,P", [(4, 65_536), (12, 30_001), (32, 200_003), (100, 50_003), (1, 5_000),
-                                 (2, 63), (224, 4_097), (16, 1_000_000)])
+                                 (2, 63), (224, 4_097), (256, 1_000), (16, 1_000_000)])
 @pytest.mark.parametrize("weighted", [False, True])
 def test_divergence_matches_oracle(combo, ref, N, P, weighted):
     rng = np.random.default_rng(N * 7 + P)
@@ -42,6 +42,26 @@ def test_divergence_matches_oracle(combo, ref, N, P, weighted):
     d = combo.workloads.dataset_sizes(N, 5, "cuda") if weighted else None
     got = gpu_divergence(combo, x, P, d)
     want = ref.aggregation_divergence(Xh, d=None if d is None else d.cpu().numpy())
+    assert np.all(np.abs(got - want) <= RTOL * want + 1e-300), (got, want)
+
+
+@pytest.mark.parametrize("N,P,Wt", [(4, 65_536, 512), (32, 200_003, 64), (16, 100_000, 128),
+                                    (100, 50_003, 64), (5, 1_000, 256), (256, 5_000, 64)])
+@pytest.mark.parametrize("weighted", [False, True])
+def test_divergence_tiled_matches_oracle(combo, ref, N, P, Wt, weighted):
+    rng = np.random.default_rng(N + P)
+    Xh = rng.normal(0, 0.02, (N, P)).astype(np.float32)
+    rows = torch.zeros((N, combo.workloads.row_pitch(P)), dtype=torch.float32, device="cuda")
+    rows[:, :P] = torch.from_numpy(Xh).cuda()
+    tiled = torch.full((combo.tiled_elems(N, P, Wt),), float("nan"), dtype=torch.float32, device="cuda")
+    combo.pack_tiled(tiled, rows, N, P, Wt)           # padding of the last tile stays NaN
+    d = combo.workloads.dataset_sizes(N, 5, "cuda") if weighted else None
+    ws = torch.empty(combo.aggregation_divergence_workspace(N, P) // 8, dtype=torch.float64, device="cuda")
+    out = torch.full((N,), float("nan"), dtype=torch.float64, device="cuda")
+    combo.aggregation_divergence_tiled(out, tiled, Wt, N, P, ws, dataset_sizes=d)
+    torch.cuda.synchronize()
+    want = ref.aggregation_divergence(Xh, d=None if d is None else d.cpu().numpy())
+    got = out.cpu().numpy()
     assert np.all(np.abs(got - want) <= RTOL * want + 1e-300), (got, want)
 
 
@@ -88,6 +108,12 @@ def test_divergence_errors(combo):
     with pytest.raises(combo.ComboError) as e:
         combo.aggregation_divergence_workspace(600, 1000)
     assert e.value.status == -3
+    with pytest.raises(combo.ComboError) as e:          # 100 rows of a 1024-column tile: too many slots
+        combo.aggregation_divergence_tiled(torch.zeros(100, dtype=torch.float64, device="cuda"),
+                                           torch.zeros(combo.tiled_elems(100, 2048, 1024), device="cuda"),
+                                           1024, 100, 2048, torch.zeros(4096 * 100, dtype=torch.float64,
+                                                                        device="cuda"))
+    assert e.value.status in (-1, -3)
     out = torch.zeros(4, dtype=torch.float64, device="cuda")
     small = torch.zeros(1, dtype=torch.float64, device="cuda")
     with pytest.raises(combo.ComboError):
