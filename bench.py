@@ -101,15 +101,23 @@ def sweep_paper(combo, P):
     stream = torch.cuda.current_stream()
     points = [("R", 10, r) for r in (1, 2, 3, 4, 6, 8, 12, 16, 29)] + \
              [("S", s, 2) for s in (1, 2, 3, 4, 6, 8, 10)]
+    ws = torch.empty(combo.aggregation_divergence_workspace(N, P) // 8, dtype=torch.float64, device="cuda")
+    d2 = torch.empty(N, dtype=torch.float64, device="cuda")
+    combo.aggregation_divergence(d2, arena[0], P, ws, stream=stream)
+    rho0 = float(d2.max().sqrt())
     for which, S, R in points:
         peers = torch.empty(N * S * R, dtype=torch.int32, device="cuda")
         combo.make_peer_table(peers, N, S, R, 0, 0)
         ms = time_kernel(lambda: combo.segment_gossip_round(arena[1], arena[0], peers, P, S, R,
                                                             stream=stream), stream)
+        # aggregation divergence (Sec. 4.3, Def. 2) after this one round from independent models
+        combo.aggregation_divergence(d2, arena[1], P, ws, stream=stream)
+        rho = float(d2.max().sqrt())
         print(json.dumps({"sweep": which, "N": N, "P": P, "S": S, "R": R, "kernel_ms": ms,
                           "rounds_per_s": 1e3 / ms,
                           "effective_GBs": 4 * (R + 2) * N * P / ms / 1e6,
-                          "compulsory_GBs": 8 * N * P / ms / 1e6}), flush=True)
+                          "compulsory_GBs": 8 * N * P / ms / 1e6,
+                          "rho_before": rho0, "rho_after_one_round": rho}), flush=True)
 
 
 def extras(combo, wl):

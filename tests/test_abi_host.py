@@ -157,3 +157,25 @@ def test_tuning_knobs(L):
     assert L.combo_tune(4, 100) == EINVAL and L.combo_tune(4, 2048) == EINVAL
     assert L.combo_tune(4, 128) == 0 and L.combo_get_tune(4) == 128 and L.combo_tune(4, 0) == 0
     assert L.combo_tune(2, 2) == EINVAL and L.combo_tune(2, 1) == 0 and L.combo_tune(2, 0) == 0
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/combo.h must compile as C99 (no C++ or HIP types in the boundary) and a C
+    translation unit that takes the address of every declared function must link against
+    the shared library."""
+    import subprocess
+    import paper_1908_07782_amd as combo
+    header = open(os.path.join(ROOT, "include", "combo.h")).read()
+    names = sorted(set(re.findall(r"\b(combo_[a-z0-9_]+)\s*\(", re.sub(r"/\*.*?\*/", "", header, flags=re.S))))
+    src = tmp_path / "use_combo.c"
+    src.write_text('#include "combo.h"\n#include <stdio.h>\ntypedef void (*fn)(void);\nint main(void) {\n  fn f[] = {'
+                   + ", ".join(f"(fn){n}" for n in names)
+                   + '};\n  printf("%d symbols %s\\n", (int)(sizeof f / sizeof f[0]), combo_strerror(COMBO_EALIAS));\n'
+                     "  return combo_tune(99, 0) == COMBO_EINVAL ? 0 : 1;\n}\n")
+    exe = tmp_path / "use_combo"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe), combo.LIB_PATH, "-Wl,-rpath," + os.path.dirname(combo.LIB_PATH),
+                    "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=60)
+    assert out.returncode == 0, out.stdout + out.stderr
+    assert f"{len(names)} symbols" in out.stdout
