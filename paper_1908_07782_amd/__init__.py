@@ -6,6 +6,7 @@ step of the round runs in the library's HIP kernels.  There is no CPU fallback: 
 shared library has not been built, importing the binding's functions raises.
 """
 from . import workloads  # noqa: F401
+from .arena import GossipArena  # noqa: F401
 from .binding import (ComboError, get_tune, lib, local_sgd_then_gossip, make_peer_table,
                       make_peer_table_pooled, peer_in_degree, make_peer_table_dynamic,
                       segment_gossip_round_dynamic, aggregation_divergence,
