@@ -201,6 +201,7 @@ def main():
                          "[N][ld]")
     ap.add_argument("--no-other-layout", action="store_true",
                     help="skip the short side measurement of the other arena layout")
+    ap.add_argument("--shape", default="", help="ad-hoc workload N,P,S,R instead of a named one")
     ap.add_argument("--tiled-cols", type=int, default=0, help="tile width of the tiled layout")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep-paper", action="store_true",
@@ -228,6 +229,9 @@ def main():
     if args.fused_mode >= 0:
         combo.tune(combo.TUNE_FUSED_MODE, args.fused_mode)
     wl = combo.workloads.WORKLOADS[args.workload]
+    if args.shape:
+        n_, p_, s_, r_ = (int(v) for v in args.shape.split(","))
+        wl = combo.workloads.small_case(n_, p_, s_, r_, scale=0.02)
     if args.replicas >= 0:
         import dataclasses
         wl = dataclasses.replace(wl, R=args.replicas, name=f"{wl.name}_R{args.replicas}")
@@ -311,11 +315,11 @@ def main():
     # g and a write of x
     alg_bytes = wl.algorithmic_bytes_per_round
     if wl.fused:
-        fused_in_kernel = tiled or (combo.get_tune(combo.TUNE_KERNEL) != 1 and
+        fused_in_kernel = tiled or (combo.round_kernel_kind(wl.N, wl.R) == 1 and
                                     combo.get_tune(combo.TUNE_FUSED_MODE) == 0)
         alg_bytes += 4 * wl.N * wl.P * (1 if fused_in_kernel else 3)
     achieved = alg_bytes / (kern_avg_ms * 1e-3) / 1e9
-    slab = tiled or combo.get_tune(combo.TUNE_KERNEL) != 1
+    slab = tiled or combo.round_kernel_kind(wl.N, wl.R) == 1
     two_pass = wl.fused and not tiled and (not slab or combo.get_tune(combo.TUNE_FUSED_MODE) == 1)
     kernel_name = ("gossip_slab_kernel" if slab else "gossip_round_kernel") + \
         (" (+ sgd_step_kernel)" if two_pass else "")

@@ -285,6 +285,9 @@ enum {
     COMBO_TUNE_SLAB_COLS = 4
 };
 int combo_tune(int key, int value);
+/* Which kernel the row-major aggregation entry points use for N workers and R replicas
+ * with aligned buffers under the current knobs: 1 = LDS-slab kernel, 0 = row-tile kernel. */
+int combo_round_kernel_kind(int32_t N, int32_t R);
 int combo_get_tune(int key); /* current value, or COMBO_EINVAL */
 
 /* Static, human-readable text for a status code. Never NULL. */

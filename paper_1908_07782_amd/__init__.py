@@ -7,7 +7,7 @@ shared library has not been built, importing the binding's functions raises.
 """
 from . import workloads  # noqa: F401
 from .arena import GossipArena  # noqa: F401
-from .binding import (ComboError, get_tune, lib, local_sgd_then_gossip, make_peer_table,
+from .binding import (ComboError, get_tune, round_kernel_kind, lib, local_sgd_then_gossip, make_peer_table,
                       make_peer_table_pooled, peer_in_degree, make_peer_table_dynamic,
                       segment_gossip_round_dynamic, aggregation_divergence,
                       aggregation_divergence_workspace, local_sgd_steps_then_gossip,

@@ -13,7 +13,7 @@ TUNE_FUSED_MODE = 2
 TUNE_KERNEL = 3
 TUNE_SLAB_COLS = 4
 
-EXPORTS = ("combo_aggregation_divergence_tiled", "combo_tiled_cols", "combo_tiled_elems", "combo_pack_tiled", "combo_unpack_tiled",
+EXPORTS = ("combo_round_kernel_kind", "combo_aggregation_divergence_tiled", "combo_tiled_cols", "combo_tiled_elems", "combo_pack_tiled", "combo_unpack_tiled",
            "combo_segment_gossip_round_tiled", "combo_local_sgd_steps_then_gossip_tiled",
            "combo_local_sgd_steps_then_gossip", "combo_aggregation_divergence", "combo_aggregation_divergence_workspace",
            "combo_make_peer_table_dynamic", "combo_segment_gossip_round_dynamic",
@@ -75,6 +75,8 @@ def lib():
         L.combo_local_sgd_steps_then_gossip_tiled.restype = ctypes.c_int
         L.combo_aggregation_divergence_tiled.argtypes = [vp, vp, i32, vp, i32, i64, vp, i64, vp]
         L.combo_aggregation_divergence_tiled.restype = ctypes.c_int
+        L.combo_round_kernel_kind.argtypes = [i32, i32]
+        L.combo_round_kernel_kind.restype = ctypes.c_int
         L.combo_tune.argtypes = [ctypes.c_int, ctypes.c_int]
         L.combo_tune.restype = ctypes.c_int
         L.combo_get_tune.argtypes = [ctypes.c_int]
@@ -93,6 +95,12 @@ def tune(key, value):
     rc = lib().combo_tune(int(key), int(value))
     if rc:
         raise ComboError(rc, "combo_tune")
+
+
+def round_kernel_kind(N, R):
+    """1 if the row-major entry points use the LDS-slab kernel for this shape, 0 for the
+    row-tile kernel."""
+    return lib().combo_round_kernel_kind(int(N), int(R))
 
 
 def get_tune(key):

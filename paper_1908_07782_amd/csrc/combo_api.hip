@@ -340,6 +340,12 @@ int combo_aggregation_divergence_tiled(double* d_dist2, const float* d_x, int32_
     return e == hipSuccess ? COMBO_OK : COMBO_EHIP;
 }
 
+int combo_round_kernel_kind(int32_t N, int32_t R) {
+    if (N < 1 || R < 0) return COMBO_EINVAL;
+    if (g_kernel.load() == 1) return 0;
+    return combo::slab_strip_cols(N, R, g_slab_cols.load()) != 0 ? 1 : 0;
+}
+
 int combo_tune(int key, int value) {
     switch (key) {
         case COMBO_TUNE_TILE_COLS:
