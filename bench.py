@@ -201,6 +201,10 @@ def main():
                          "[N][ld]")
     ap.add_argument("--no-other-layout", action="store_true",
                     help="skip the short side measurement of the other arena layout")
+    ap.add_argument("--one-launch", type=int, default=0,
+                    help="0 (default): combo_make_peer_table, then the table-driven round; 1: a step is "
+                         "ONE combo_round_hashed launch (peer selection inside the kernel; faster only "
+                         "for launch-bound sizes)")
     ap.add_argument("--shape", default="", help="ad-hoc workload N,P,S,R instead of a named one")
     ap.add_argument("--tiled-cols", type=int, default=0, help="tile width of the tiled layout")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -250,6 +254,8 @@ def main():
     peers = torch.empty(max(wl.N * wl.S * wl.R, 1), dtype=torch.int32, device=dev)
     stream = torch.cuda.current_stream()
 
+    used = {}
+
     def run_layout(layout, steps, warmup):
         """Time `steps` steps in one arena layout; returns (wall seconds, kernel ms list, Wt)."""
         is_tiled = layout == "tiled"
@@ -266,8 +272,22 @@ def main():
             grads.normal_(0.0, wl.grad_std)          # layout-agnostic: i.i.d. values
         state = {"cur": 0, "round": 0}
 
+        one_launch = bool(args.one_launch) and wl.R <= 8 and \
+            (is_tiled or combo.round_kernel_kind(wl.N, wl.R) == 1)
+        used["one_launch"] = one_launch
+        g1 = None if grads is None else grads.reshape((1,) + tuple(grads.shape))
+
         def step(ev=None):
             cur, rnd = state["cur"], state["round"]
+            if one_launch:
+                if ev is not None:
+                    ev[0].record(stream)
+                combo.round_hashed(arena[1 - cur], arena[cur], wl.N, wl.P, wl.S, wl.R, wl.hash_seed, rnd,
+                                   grads=g1, lr=wl.lr, tile_cols=wt, stream=stream)
+                if ev is not None:
+                    ev[1].record(stream)
+                state["cur"], state["round"] = 1 - cur, rnd + 1
+                return
             combo.make_peer_table(peers, wl.N, wl.S, wl.R, wl.hash_seed, rnd, stream=stream)
             if ev is not None:
                 ev[0].record(stream)
@@ -301,6 +321,7 @@ def main():
 
     tiled = args.layout == "tiled"
     wall, kern_ms, Wt = run_layout(args.layout, args.steps, args.warmup)
+    one_launch = used["one_launch"]
     other = None
     if not args.no_other_layout:
         other_name = "rows" if tiled else "tiled"
@@ -315,12 +336,13 @@ def main():
     # g and a write of x
     alg_bytes = wl.algorithmic_bytes_per_round
     if wl.fused:
-        fused_in_kernel = tiled or (combo.round_kernel_kind(wl.N, wl.R) == 1 and
-                                    combo.get_tune(combo.TUNE_FUSED_MODE) == 0)
+        fused_in_kernel = tiled or one_launch or (combo.round_kernel_kind(wl.N, wl.R) == 1 and
+                                                  combo.get_tune(combo.TUNE_FUSED_MODE) == 0)
         alg_bytes += 4 * wl.N * wl.P * (1 if fused_in_kernel else 3)
     achieved = alg_bytes / (kern_avg_ms * 1e-3) / 1e9
     slab = tiled or combo.round_kernel_kind(wl.N, wl.R) == 1
-    two_pass = wl.fused and not tiled and (not slab or combo.get_tune(combo.TUNE_FUSED_MODE) == 1)
+    two_pass = wl.fused and not tiled and not one_launch and \
+        (not slab or combo.get_tune(combo.TUNE_FUSED_MODE) == 1)
     kernel_name = ("gossip_slab_kernel" if slab else "gossip_round_kernel") + \
         (" (+ sgd_step_kernel)" if two_pass else "")
     out = {
@@ -337,7 +359,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": wl.name, "N": wl.N, "P": wl.P, "S": wl.S, "R": wl.R,
-                   "fused_local_step": wl.fused, "layout": args.layout, "tiled_cols": Wt, "kernel": combo.get_tune(combo.TUNE_KERNEL),
+                   "fused_local_step": wl.fused, "one_launch_per_round": one_launch, "layout": args.layout, "tiled_cols": Wt, "kernel": combo.get_tune(combo.TUNE_KERNEL),
                    "slab_cols": combo.get_tune(combo.TUNE_SLAB_COLS),
                    "fused_mode": combo.get_tune(combo.TUNE_FUSED_MODE),
                    "tile_cols": combo.get_tune(combo.TUNE_TILE_COLS),

@@ -232,6 +232,25 @@ int combo_local_sgd_steps_then_gossip_tiled(float* d_dst, const float* d_src, co
                                             void* stream);
 
 /*
+ * A whole iteration in ONE launch, without a peer table: peer selection exactly as
+ * combo_make_peer_table(seed, round) would make it (every workgroup draws the peer lists
+ * it needs from the counter-based hash while its loads are in flight), the optional tau
+ * local SGD steps, and the aggregation.  Results are identical, bit for bit, to
+ * combo_make_peer_table followed by combo_local_sgd_steps_then_gossip (or its tiled form).
+ *   tile_cols  0: row-major d_dst/d_src/d_grads with pitch ld; else the tiled layout
+ *              [T][N][tile_cols] (ld is ignored)
+ *   d_grads    tau matrices in the same layout, back to back; may be NULL when tau == 0
+ *   d_src      never modified
+ * Errors: COMBO_EINVAL / COMBO_EALIAS as for the table-driven calls; COMBO_ERANGE when the
+ * in-kernel draw cannot be used: R > 8, buffers not 16-byte aligned, ld % 4 != 0, or the
+ * N-row slab does not fit in LDS - use the table-driven entry points then.
+ */
+int combo_round_hashed(float* d_dst, const float* d_src, const float* d_grads, int32_t tau,
+                       float lr, int64_t ld, int32_t tile_cols, const float* d_dataset_sizes,
+                       int32_t N, int64_t P, int32_t S, int32_t R, uint64_t seed, uint64_t round,
+                       void* stream);
+
+/*
  * Aggregation divergence (Sec. 4.3, Definition 2): how far each worker's model is from the
  * aggregate of ALL workers (the FedAvg output).
  *     mean[e]     = sum_w d[w]*x[w][e] / sum_w d[w]      (d = 1 when d_dataset_sizes is NULL)

@@ -13,7 +13,7 @@ TUNE_FUSED_MODE = 2
 TUNE_KERNEL = 3
 TUNE_SLAB_COLS = 4
 
-EXPORTS = ("combo_round_kernel_kind", "combo_aggregation_divergence_tiled", "combo_tiled_cols", "combo_tiled_elems", "combo_pack_tiled", "combo_unpack_tiled",
+EXPORTS = ("combo_round_hashed", "combo_round_kernel_kind", "combo_aggregation_divergence_tiled", "combo_tiled_cols", "combo_tiled_elems", "combo_pack_tiled", "combo_unpack_tiled",
            "combo_segment_gossip_round_tiled", "combo_local_sgd_steps_then_gossip_tiled",
            "combo_local_sgd_steps_then_gossip", "combo_aggregation_divergence", "combo_aggregation_divergence_workspace",
            "combo_make_peer_table_dynamic", "combo_segment_gossip_round_dynamic",
@@ -75,6 +75,8 @@ def lib():
         L.combo_local_sgd_steps_then_gossip_tiled.restype = ctypes.c_int
         L.combo_aggregation_divergence_tiled.argtypes = [vp, vp, i32, vp, i32, i64, vp, i64, vp]
         L.combo_aggregation_divergence_tiled.restype = ctypes.c_int
+        L.combo_round_hashed.argtypes = [vp, vp, vp, i32, f32, i64, i32, vp, i32, i64, i32, i32, u64, u64, vp]
+        L.combo_round_hashed.restype = ctypes.c_int
         L.combo_round_kernel_kind.argtypes = [i32, i32]
         L.combo_round_kernel_kind.restype = ctypes.c_int
         L.combo_tune.argtypes = [ctypes.c_int, ctypes.c_int]
@@ -363,3 +365,28 @@ def aggregation_divergence_tiled(dist2, x, tile_cols, N, P, workspace, dataset_s
     if rc:
         raise ComboError(rc, "combo_aggregation_divergence_tiled")
     return dist2
+
+
+def round_hashed(dst, src, N, P, S, R, seed, rnd, *, grads=None, lr=0.0, tile_cols=0,
+                 dataset_sizes=None, stream=None):
+    """combo_round_hashed: peer selection + optional local steps + aggregation in one
+    launch.  Row-major: dst/src are (N, ld)-strided, grads (tau, N, ld); tiled: flat buffers."""
+    tau = 0 if grads is None else int(grads.shape[0])
+    if tile_cols:
+        n = tiled_elems(N, P, tile_cols)
+        ld = tile_cols
+        pd, ps = _flat(dst, n, "dst"), _flat(src, n, "src")
+        pg = _flat(grads.reshape(-1), n * tau, "grads") if tau else None
+    else:
+        ld = _matrix(src, "src")
+        if _matrix(dst, "dst") != ld or dst.shape[0] != N or src.shape[0] != N:
+            raise ValueError("dst must have src's row count and pitch")
+        pd, ps = _dev_ptr(dst, torch.float32, "dst"), _dev_ptr(src, torch.float32, "src")
+        pg = _dev_ptr(grads, torch.float32, "grads") if tau else None
+    rc = lib().combo_round_hashed(pd, ps, pg, tau, ctypes.c_float(lr), ld, tile_cols,
+                                  _dev_ptr(dataset_sizes, torch.float32, "dataset_sizes", optional=True),
+                                  N, P, S, R, ctypes.c_uint64(seed), ctypes.c_uint64(rnd),
+                                  _stream_ptr(stream))
+    if rc:
+        raise ComboError(rc, "combo_round_hashed")
+    return dst

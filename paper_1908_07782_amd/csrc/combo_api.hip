@@ -5,6 +5,7 @@
 #include <atomic>
 
 #include "combo_internal.h"
+#include "round_device.h"
 
 namespace {
 
@@ -44,7 +45,7 @@ int check_round_args(const float* dst, const float* src, int64_t ld, const int32
 int enqueue_round(float* dst, const float* src, const float* grad, float lr, int64_t ld,
                   const int32_t* peers, const float* dsz, int32_t N, int64_t P, int32_t S,
                   int32_t R, Plan plan, hipStream_t st, const uint8_t* status = nullptr,
-                  int32_t tau = 1, int arena_tile = 0) {
+                  int32_t tau = 1, int arena_tile = 0, bool hashed = false, uint64_t hash_sr = 0) {
     const int tile_cols = g_tile_cols.load();
     const bool swizzle = g_swizzle.load() != 0;
     combo::RoundArgs a;
@@ -73,6 +74,9 @@ int enqueue_round(float* dst, const float* src, const float* grad, float lr, int
         const int64_t tiles = (P + arena_tile - 1) / arena_tile;
         a.grad_slice = tiles * (int64_t)N * (int64_t)arena_tile;
     }
+    a.hash_sr = hash_sr;
+    if (hashed)
+        return combo::launch_round_slab_hashed(a, plan.cols, st) == hipSuccess ? COMBO_OK : COMBO_EHIP;
     if (plan.kind == kPlanSlab)
         return combo::launch_round_slab(a, plan.cols, st) == hipSuccess ? COMBO_OK : COMBO_EHIP;
     if (status != nullptr)
@@ -297,6 +301,39 @@ int combo_local_sgd_steps_then_gossip_tiled(float* d_dst, const float* d_src, co
     return enqueue_round(d_dst, d_src, tau > 0 ? d_grads : nullptr, lr, tile_cols, d_peers,
                          d_dataset_sizes, N, P, S, R, Plan{kPlanSlab, tile_cols}, (hipStream_t)stream,
                          nullptr, tau, tile_cols);
+}
+
+int combo_round_hashed(float* d_dst, const float* d_src, const float* d_grads, int32_t tau, float lr,
+                       int64_t ld, int32_t tile_cols, const float* d_dataset_sizes, int32_t N,
+                       int64_t P, int32_t S, int32_t R, uint64_t seed, uint64_t round, void* stream) {
+    if (N < 1 || S < 1 || P < 1 || (int64_t)S > P || R < 0 || R > N - 1) return COMBO_EINVAL;
+    if (d_dst == nullptr || d_src == nullptr || tau < 0 || (tau > 0 && d_grads == nullptr))
+        return COMBO_EINVAL;
+    if (R > combo::kMaxHashedR) return COMBO_ERANGE;
+    uint64_t elems;
+    int W;
+    if (tile_cols != 0) {
+        if (!tile_cols_ok(tile_cols)) return COMBO_EINVAL;
+        elems = (uint64_t)tiled_elems(N, P, tile_cols);
+        W = tile_cols;
+        if (combo::slab_strip_cols(N, R, W) != W) return COMBO_ERANGE;
+    } else {
+        if (ld < P) return COMBO_EINVAL;
+        elems = (uint64_t)N * (uint64_t)ld;
+        W = combo::slab_strip_cols(N, R, g_slab_cols.load());
+        if (W == 0 || ld % 4 != 0) return COMBO_ERANGE;
+    }
+    if (!aligned16(d_dst) || !aligned16(d_src) || !aligned16(d_grads)) return COMBO_ERANGE;
+    if (((uint64_t)P + (uint64_t)W - 1) / (uint64_t)W > 0x7FFFFFFFull) return COMBO_ERANGE;
+    const uint64_t bytes = elems * sizeof(float);
+    if (overlaps(d_dst, bytes, d_src, bytes)) return COMBO_EALIAS;
+    if (tau > 0 && (overlaps(d_grads, bytes * (uint64_t)tau, d_src, bytes) ||
+                    overlaps(d_grads, bytes * (uint64_t)tau, d_dst, bytes)))
+        return COMBO_EALIAS;
+    const uint64_t h_sr = combo::hash_take_in(combo::hash_finalise(seed + combo::kHashGamma), round);
+    return enqueue_round(d_dst, d_src, tau > 0 ? d_grads : nullptr, lr, tile_cols ? tile_cols : ld,
+                         nullptr, d_dataset_sizes, N, P, S, R, Plan{kPlanSlab, W}, (hipStream_t)stream,
+                         nullptr, tau, tile_cols, true, h_sr);
 }
 
 int64_t combo_aggregation_divergence_workspace(int32_t N, int64_t P) {

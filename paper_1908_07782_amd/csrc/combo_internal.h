@@ -31,6 +31,7 @@ struct RoundArgs {
     int32_t tau;             // number of fused local steps (gradient slices)
     int64_t grad_slice;      // elements between consecutive gradient slices
     int32_t tile_shift;      // 0: row-major [N][ld]; else log2(Wt) of the tiled layout [T][N][Wt]
+    uint64_t hash_sr;        // table-free rounds: peer-hash state after seed and round
 };
 
 // launchers (defined in gossip_round.hip / peer_table.hip); return hipGetLastError()
@@ -65,6 +66,10 @@ hipError_t launch_unpack_tiled(float* rows, int64_t ld, const float* tiled, int3
 // LDS.  slab_strip_cols() picks the strip width for N workers (0: does not fit in LDS).
 int slab_strip_cols(int32_t N, int32_t R, int requested);
 hipError_t launch_round_slab(const RoundArgs& a, int strip_cols, hipStream_t st);
+// the same kernel drawing its peers in-kernel from a.hash_sr (R <= 8, no table)
+hipError_t launch_round_slab_hashed(const RoundArgs& a, int strip_cols, hipStream_t st);
+size_t slab_lds_bytes(int32_t N, int32_t R, int strip_cols);
+int slab_threads(int32_t N, int strip_cols);
 
 // number of workgroups launch_round would use, or 0 if that exceeds the grid limit
 uint64_t round_grid_size(int32_t N, int64_t P, int tile_cols, bool swizzle);

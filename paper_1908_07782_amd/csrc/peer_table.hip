@@ -8,24 +8,17 @@
 // thousand entries per round), so the kernel is launch-latency bound by construction;
 // what matters is that it is a pure function of (seed, round, w, s, j).
 #include "combo_internal.h"
+#include "round_device.h"
 
 namespace combo {
 namespace {
 
-constexpr uint64_t kGamma = 0x9E3779B97F4A7C15ull;   // SplitMix64 increment
+constexpr uint64_t kGamma = kHashGamma;
 
-__device__ __forceinline__ uint64_t finalise(uint64_t z) {
-    // output function of SplitMix64: two xor-shift-multiply rounds and a last xor-shift
-    z ^= z >> 30;
-    z *= 0xBF58476D1CE4E5B9ull;
-    z ^= z >> 27;
-    z *= 0x94D049BB133111EBull;
-    z ^= z >> 31;
-    return z;
-}
+__device__ __forceinline__ uint64_t finalise(uint64_t z) { return hash_finalise(z); }
 
 __device__ __forceinline__ uint64_t take_in(uint64_t h, uint64_t counter) {
-    return finalise((h ^ counter) + kGamma);
+    return hash_take_in(h, counter);
 }
 
 __global__ __launch_bounds__(64) void peer_table_kernel(int32_t* __restrict__ peers, int32_t N,

@@ -55,6 +55,52 @@ __device__ __forceinline__ v4f div4(v4f a, float d) {
     return y;
 }
 
+// ---- the counter-based peer hash (see combo_make_peer_table in the header) ------------
+constexpr uint64_t kHashGamma = 0x9E3779B97F4A7C15ull;   // SplitMix64 increment
+
+__host__ __device__ __forceinline__ uint64_t hash_finalise(uint64_t z) {
+    // output function of SplitMix64: two xor-shift-multiply rounds and a last xor-shift
+    z ^= z >> 30;
+    z *= 0xBF58476D1CE4E5B9ull;
+    z ^= z >> 27;
+    z *= 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return z;
+}
+
+__host__ __device__ __forceinline__ uint64_t hash_take_in(uint64_t h, uint64_t counter) {
+    return hash_finalise((h ^ counter) + kHashGamma);
+}
+
+constexpr int kMaxHashedR = 8;   // replica counts the in-kernel peer draw supports
+
+// The R providers of (worker w, segment s) without a table: the first R steps of the
+// Fisher-Yates shuffle of the N-1 other workers, on a virtual array whose displaced
+// slots (at most one per step) are kept in registers.  Same picks, same order as the
+// peer-table kernel.  h_sr = hash state after seed and round.
+__device__ __forceinline__ void draw_peers(uint64_t h_sr, int32_t w, int32_t s, int32_t N, int32_t R,
+                                           int32_t (&out)[kMaxHashedR]) {
+    const uint64_t h = hash_take_in(hash_take_in(h_sr, (uint64_t)w), (uint64_t)s);
+    const int32_t M = N - 1;
+    int32_t pos[kMaxHashedR], val[kMaxHashedR];
+#pragma unroll
+    for (int j = 0; j < kMaxHashedR; ++j) {
+        if (j < R) {
+            const uint64_t word = hash_take_in(h, (uint64_t)j);
+            const int32_t r = j + (int32_t)(((word >> 32) * (uint64_t)(uint32_t)(M - j)) >> 32);
+            int32_t at_r = r, at_j = j;              // current contents of slots r and j
+#pragma unroll
+            for (int k = 0; k < j; ++k) {            // the latest displacement of a slot wins
+                if (pos[k] == r) at_r = val[k];
+                if (pos[k] == j) at_j = val[k];
+            }
+            out[j] = at_r + (at_r >= w ? 1 : 0);     // skip over w itself
+            pos[j] = r;                              // slot r now holds what slot j held
+            val[j] = at_j;
+        }
+    }
+}
+
 // segment of column e: floor(e / L), the last segment also owning the remainder (Eq. 1)
 __device__ __forceinline__ int32_t segment_of(int64_t e, const RoundArgs& a) {
     uint64_t q;
@@ -86,10 +132,17 @@ __device__ __forceinline__ float served_value(const RoundArgs& a, int32_t row, i
 
 // Eq. (3) for one element of any segment: used for tiles that contain a segment
 // boundary, ragged row ends and unaligned buffers
-template <bool WEIGHTED, bool FUSED>
+template <bool WEIGHTED, bool FUSED, bool HASHED = false>
 __device__ __forceinline__ void average_element(const RoundArgs& a, int32_t w, int64_t e) {
     const int32_t s = segment_of(e, a);
-    const int32_t* pl = a.peers + ((size_t)w * (size_t)a.S + (size_t)s) * (size_t)a.R;
+    int32_t drawn[kMaxHashedR];
+    const int32_t* pl;
+    if (HASHED) {
+        draw_peers(a.hash_sr, w, s, a.N, a.R, drawn);
+        pl = drawn;
+    } else {
+        pl = a.peers + ((size_t)w * (size_t)a.S + (size_t)s) * (size_t)a.R;
+    }
     const float own = served_value<FUSED>(a, w, e);
     float out;
     if (!WEIGHTED) {

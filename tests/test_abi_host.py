@@ -105,6 +105,25 @@ def test_divergence_argument_errors(L):
     assert f(FAKE_A, FAKE_B, 1024, None, 4, 1000, ctypes.c_void_p(0x30000004), 10**6, None) == EINVAL
 
 
+def test_hashed_round_argument_errors(L):
+    f = L.combo_round_hashed
+
+    def call(dst=FAKE_A, src=FAKE_B, grads=None, tau=0, ld=1024, tile=0, N=4, P=1000, S=4, R=2):
+        return f(dst, src, grads, tau, ctypes.c_float(0.1), ld, tile, None, N, P, S, R, 1, 2, None)
+
+    assert call(R=4) == EINVAL and call(S=0) == EINVAL and call(dst=None) == EINVAL
+    assert call(tau=1) == EINVAL                    # gradients missing
+    assert call(tau=-1) == EINVAL
+    assert call(ld=999) == EINVAL
+    assert call(tile=100) == EINVAL
+    assert call(N=20, R=9) == ERANGE                # in-kernel draw supports R <= 8
+    assert call(ld=1001, P=1001) == ERANGE          # pitch not a multiple of 4
+    assert call(dst=ctypes.c_void_p(0x10000004)) == ERANGE
+    assert call(N=300, R=2) == ERANGE               # slab does not fit
+    assert call(dst=FAKE_B) == EALIAS
+    assert call(grads=FAKE_B, tau=1) == EALIAS
+
+
 def test_round_argument_errors(L):
     f = L.combo_segment_gossip_round
     ok = dict(N=4, P=1000, S=4, R=2, ld=1024)
