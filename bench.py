@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
 
 def kernel_source_digest():
     h = hashlib.sha256()
-    for f in ("gossip_slab.hip", "gossip_round.hip", "round_device.h", "combo_internal.h"):
+    for f in ("gossip_slab_kernel.h", "gossip_slab.hip", "round_device.h", "combo_internal.h"):
         h.update(open(os.path.join(ROOT, "paper_1908_07782_amd", "csrc", f), "rb").read())
     return h.hexdigest()[:16]
 

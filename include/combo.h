@@ -125,6 +125,25 @@ int combo_segment_gossip_round(float* d_dst, const float* d_src, int64_t ld,
                                int32_t N, int64_t P, int32_t S, int32_t R, void* stream);
 
 /*
+ * Local update, then the round (Sec. 4.1 steps 1, 3, 4): first EVERY worker takes one
+ * SGD step with the given gradient, x' = x - lr*g (product rounded, then the
+ * difference), and only then Eq. (3) is applied to the stepped parameters x' exactly as
+ * in combo_segment_gossip_round.
+ *
+ *   d_src   in/out, device, float32[N][ld]: the pre-update parameters x.  On return its
+ *           contents are x or x', unspecified which (the fused kernel forms x' on the
+ *           fly and leaves d_src alone; the two-pass fallback steps d_src in place).
+ *           Callers ping-pong the buffers, so the old front buffer is dead either way.
+ *   d_grad  in, device, float32[N][ld], same pitch; not modified.
+ * Errors: as combo_segment_gossip_round, plus COMBO_EINVAL for a NULL d_grad and
+ * COMBO_EALIAS if d_grad overlaps d_src or d_dst.
+ */
+int combo_local_sgd_then_gossip(float* d_dst, float* d_src, const float* d_grad, float lr,
+                                int64_t ld, const int32_t* d_peers,
+                                const float* d_dataset_sizes, int32_t N, int64_t P, int32_t S,
+                                int32_t R, void* stream);
+
+/*
  * The same with a communication interval tau (Sec. 4.1 step 1: several SGD rounds between
  * two synchronisations): tau steps x <- x - lr*g_t, t = 0..tau-1 in that order, each with
  * its own given gradient, then the round on the result.
@@ -169,25 +188,6 @@ int combo_segment_gossip_round_dynamic(float* d_dst, const float* d_src, int64_t
                                        const int32_t* d_peers, const float* d_dataset_sizes,
                                        const uint8_t* d_status, int32_t N, int64_t P, int32_t S,
                                        int32_t R, void* stream);
-
-/*
- * Local update, then the round (Sec. 4.1 steps 1, 3, 4): first EVERY worker takes one
- * SGD step with the given gradient, x' = x - lr*g (product rounded, then the
- * difference), and only then Eq. (3) is applied to the stepped parameters x' exactly as
- * in combo_segment_gossip_round.
- *
- *   d_src   in/out, device, float32[N][ld]: the pre-update parameters x.  On return its
- *           contents are x or x', unspecified which (the fused kernel forms x' on the
- *           fly and leaves d_src alone; the two-pass fallback steps d_src in place).
- *           Callers ping-pong the buffers, so the old front buffer is dead either way.
- *   d_grad  in, device, float32[N][ld], same pitch; not modified.
- * Errors: as combo_segment_gossip_round, plus COMBO_EINVAL for a NULL d_grad and
- * COMBO_EALIAS if d_grad overlaps d_src or d_dst.
- */
-int combo_local_sgd_then_gossip(float* d_dst, float* d_src, const float* d_grad, float lr,
-                                int64_t ld, const int32_t* d_peers,
-                                const float* d_dataset_sizes, int32_t N, int64_t P, int32_t S,
-                                int32_t R, void* stream);
 
 /*
  * Tiled arena layout.  Instead of row-major [N][ld], a parameter matrix may be kept as
@@ -255,16 +255,15 @@ int combo_round_hashed(float* d_dst, const float* d_src, const float* d_grads, i
  * aggregate of ALL workers (the FedAvg output).
  *     mean[e]     = sum_w d[w]*x[w][e] / sum_w d[w]      (d = 1 when d_dataset_sizes is NULL)
  *     d_dist2[w]  = sum_e (x[w][e] - mean[e])^2
- * evaluated in binary64 (column means in worker order; squared differences summed by a
- * fixed tree, so repeated calls give identical bits).  The rho of Definition 2 is bounded
+ * evaluated in binary64 in a fixed order (the mean as sum * (1 / sum of d); no floating-
+ * point atomics), so repeated calls give identical bits.  The rho of Definition 2 is bounded
  * below by max_w sqrt(d_dist2[w]).
  *   d_dist2      out, device, float64[N]
  *   d_x          in,  device, float32[N][ld]
  *   d_workspace  scratch, device, 8-byte aligned, at least
  *                combo_aggregation_divergence_workspace(N, P) bytes; contents irrelevant
  *                before and after the call
- * combo_aggregation_divergence_tiled reads a tiled matrix [T][N][tile_cols] instead
- *.
+ * combo_aggregation_divergence_tiled reads a tiled matrix [T][N][tile_cols] instead.
  * Errors: COMBO_EINVAL for bad sizes, NULL pointers, a workspace that is too small or
  * misaligned; COMBO_ERANGE for N > 256, or when N rows of a tile exceed the kernel's
  * register slots (N * tile_cols > 16384).

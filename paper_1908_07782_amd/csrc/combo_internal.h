@@ -9,7 +9,6 @@ namespace combo {
 
 constexpr int kThreads = 256;          // 4 wavefronts of 64 lanes per workgroup
 constexpr int kXcds = 8;               // accelerator complex dies of one MI355X
-constexpr int kMaxTemplatedR = 8;      // replica counts with a fully unrolled kernel
 
 // Arguments of one aggregation round, passed by value to the kernels.
 struct RoundArgs {
@@ -34,7 +33,7 @@ struct RoundArgs {
     uint64_t hash_sr;        // table-free rounds: peer-hash state after seed and round
 };
 
-// launchers (defined in gossip_round.hip / peer_table.hip); return hipGetLastError()
+// launchers; each returns hipGetLastError() of its launch
 hipError_t launch_round(const RoundArgs& a, int tile_cols, bool vec, hipStream_t st);
 hipError_t launch_round_dynamic_elementwise(const RoundArgs& a, hipStream_t st);
 hipError_t launch_peer_table_dynamic(int32_t* peers, const uint8_t* status, int32_t N, int32_t S,

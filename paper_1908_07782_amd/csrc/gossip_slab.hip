@@ -1,22 +1,5 @@
-// Gather-average round, LDS-slab form: Eq. (3) / Eq. (4) of the segmented-gossip paper
-// with every front-buffer element fetched exactly once.
-//
-// One workgroup owns a strip of `W` consecutive columns of ALL N workers.  It first
-// copies the N x W slab of the front buffer into LDS (each wave instruction moves whole
-// 128-bit words of one row: fully coalesced), together with the strip's peer list
-// peers[.][s][.] and, for weighted rounds, the dataset sizes.  After one barrier every
-// output element is formed from LDS: own value, then the R providers in table order,
-// then the scale - the same fixed order as the row-tile kernel - and streamed to the
-// back buffer with non-temporal 128-bit stores.  HBM and L2 see one read and one write
-// per element whatever R is; the R+1 reads per output are LDS reads.
-//
-// With the local update fused in, the slab is filled with the parameters after the tau
-// SGD steps x <- x - lr*g_t (each gradient slice read once, product rounded before the
-// difference, slices in order), so peers are served post-update values as Sec. 4.1
-// requires, and the front buffer itself is left untouched.  (Callers pass tau >= 1.)
-//
-// A strip that contains a segment boundary or the ragged end of the row (at most S
-// strips per round) falls back to per-element evaluation from global memory.
+// Table-driven instantiations of the LDS-slab aggregation kernel (gossip_slab_kernel.h)
+// and the host-side choices around it: strip width, workgroup size, LDS budget.
 #include "gossip_slab_kernel.h"
 
 namespace combo {

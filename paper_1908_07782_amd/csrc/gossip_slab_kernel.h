@@ -1,5 +1,25 @@
-// The LDS-slab aggregation kernel template (included by the translation units that
-// instantiate it: the table-driven variants and the table-free ones).
+// Gather-average round, LDS-slab form: Eq. (3) / Eq. (4) of the segmented-gossip paper
+// with every front-buffer element fetched exactly once.
+//
+// One workgroup owns a strip of `W` consecutive columns of ALL N workers.  It first
+// copies the N x W slab of the front buffer into LDS (each wave instruction moves whole
+// 128-bit words of one row: fully coalesced), together with the strip's peer list
+// peers[.][s][.] and, for weighted rounds, the dataset sizes.  After one barrier every
+// output element is formed from LDS: own value, then the R providers in table order,
+// then the scale - the same fixed order as the row-tile kernel - and streamed to the
+// back buffer with non-temporal 128-bit stores.  HBM and L2 see one read and one write
+// per element whatever R is; the R+1 reads per output are LDS reads.
+//
+// With the local update fused in, the slab is filled with the parameters after the tau
+// SGD steps x <- x - lr*g_t (each gradient slice read once, product rounded before the
+// difference, slices in order), so peers are served post-update values as Sec. 4.1
+// requires, and the front buffer itself is left untouched.  (Callers pass tau >= 1.)
+//
+// A strip that contains a segment boundary or the ragged end of the row (at most S
+// strips per round) falls back to per-element evaluation from global memory.
+//
+// This header holds the kernel template; it is included by the translation units that
+// instantiate it (the table-driven variants and the table-free ones).
 #ifndef COMBO_GOSSIP_SLAB_KERNEL_H_
 #define COMBO_GOSSIP_SLAB_KERNEL_H_
 
@@ -11,11 +31,10 @@ namespace {
 
 constexpr int kBatch = 4;   // 128-bit loads kept in flight per thread while filling the slab
 
-// Workgroup size of the slab kernel: 256 or 512 threads, chosen on the host so that a
-// thread moves about two 128-bit words (measured on MI355X: 8 KiB slabs with 256 threads
-// and 16 KiB slabs with 512 threads beat every other combination of 128..1024 threads
-// and 4..64 KiB slabs).
-constexpr int kSlabThreadsMax = 512;
+// Workgroup size of the slab kernel (template parameter): 256 or 512 threads, chosen on
+// the host so that a thread moves about two 128-bit words (measured on MI355X: 8 KiB slabs
+// with 256 threads and 16 KiB slabs with 512 threads beat every other combination of
+// 128..1024 threads and 4..64 KiB slabs).
 
 // every front-buffer element is read once, so the slab fill uses streaming loads
 __device__ __forceinline__ v4f load4_slab(const float* p) {
