@@ -54,54 +54,75 @@ __global__ __launch_bounds__(64) void peer_table_kernel(int32_t* __restrict__ pe
 // Pooled selection (Sec. 4.1 step 2 as written): all S*R requests of a worker draw from
 // one queue holding a random permutation of the other workers; an empty queue is
 // replaced by the next permutation; a request takes the first queue element that its
-// segment has not picked yet, skipped elements keep their place.  The draw is a
-// dependent chain per worker, so one lane of one wavefront walks it with the queue in
-// LDS: queue[head..M) are the elements still in the pool.
+// segment has not picked yet, skipped elements keep their place.  Every permutation is
+// consumed completely, so ceil(S*R / (N-1)) of them are needed: the wavefront loops over
+// them; for each one all lanes fill the queue and evaluate the hash words of the
+// Fisher-Yates steps in parallel (LDS, 16-bit entries), then lane 0 applies the swaps and
+// serves requests until the queue is empty.  queue[head..M) are the elements still in
+// the pool.
 constexpr uint64_t kPoolTag = 0x706F6F6C65642121ull;
 
 __global__ __launch_bounds__(64) void peer_table_pooled_kernel(int32_t* __restrict__ peers,
                                                                int32_t N, int32_t S, int32_t R,
                                                                uint64_t seed, uint64_t round) {
-    extern __shared__ int32_t queue[];           // N-1 slots
-    if (threadIdx.x != 0) return;
+    extern __shared__ uint16_t pool_lds[];
     const int32_t M = N - 1;
+    uint16_t* queue = pool_lds;                  // [M] worker ids
+    uint16_t* partner = pool_lds + M;            // [M] swap partner of every shuffle step
     const int32_t w = (int32_t)blockIdx.x;
+    const int lane = (int)threadIdx.x;
     uint64_t hw = finalise((seed ^ kPoolTag) + kGamma);
     hw = take_in(hw, round);
     hw = take_in(hw, (uint64_t)w);
-    int32_t head = M;                             // empty pool
-    uint64_t epoch = 0;
-    for (int32_t s = 0; s < S; ++s) {
-        int32_t* picks = peers + ((size_t)w * (size_t)S + (size_t)s) * (size_t)R;
-        for (int32_t j = 0; j < R; ++j) {
-            if (head == M) {
-                // next permutation of the others: full Fisher-Yates
-                for (int32_t i = 0; i < M; ++i) queue[i] = i + (i >= w ? 1 : 0);
-                const uint64_t he = take_in(hw, epoch);
-                for (int32_t i = 0; i + 1 < M; ++i) {
-                    const uint64_t word = take_in(he, (uint64_t)i);
-                    const int32_t r = i + (int32_t)(((word >> 32) * (uint64_t)(uint32_t)(M - i)) >> 32);
-                    const int32_t t = queue[i];
-                    queue[i] = queue[r];
-                    queue[r] = t;
-                }
-                head = 0;
-                ++epoch;
-            }
-            // first pool element this segment has not picked; at most j elements are skipped
-            int32_t pos = head;
-            for (; pos < M; ++pos) {
-                const int32_t c = queue[pos];
-                bool taken = false;
-                for (int32_t k = 0; k < j; ++k) taken = taken || (picks[k] == c);
-                if (!taken) break;
-            }
-            if (pos == M) pos = M - 1;            // unreachable while R <= N-1; keeps indices in range
-            const int32_t c = queue[pos];
-            for (int32_t q = pos; q > head; --q) queue[q] = queue[q - 1];   // skipped keep their order
-            ++head;
-            picks[j] = c;
+
+    const int64_t requests = (int64_t)S * R;
+    const int64_t epochs = (requests + M - 1) / M;
+    int64_t served = 0;                           // lane 0: requests done so far
+    for (int64_t epoch = 0; epoch < epochs; ++epoch) {
+        const uint64_t he = take_in(hw, (uint64_t)epoch);
+        for (int32_t i = lane; i < M; i += 64) {
+            queue[i] = (uint16_t)(i + (i >= w ? 1 : 0));
+            const uint64_t word = take_in(he, (uint64_t)i);
+            partner[i] = (uint16_t)(i + (int32_t)(((word >> 32) * (uint64_t)(uint32_t)(M - i)) >> 32));
         }
+        __syncthreads();
+        if (lane == 0) {
+            for (int32_t i = 0; i + 1 < M; ++i) {           // full Fisher-Yates
+                const int32_t r = partner[i];
+                const uint16_t t = queue[i];
+                queue[i] = queue[r];
+                queue[r] = t;
+            }
+            // Only the picks this segment received from EARLIER permutations can reappear in
+            // the new queue (picks taken from this queue have left it): copy those once into
+            // the now unused partner array and compare against them while the segment lasts.
+            int32_t carried = (int32_t)(served % R);
+            {
+                const int32_t* seg = peers + ((size_t)w * (size_t)S) * (size_t)R + (size_t)(served - carried);
+                for (int32_t k = 0; k < carried; ++k) partner[k] = (uint16_t)seg[k];
+            }
+            int32_t head = 0;
+            while (head < M && served < requests) {
+                const int32_t j = (int32_t)(served % R);
+                if (j == 0) carried = 0;          // a new segment starts with an empty pick set
+                int32_t* picks = peers + ((size_t)w * (size_t)S) * (size_t)R + (size_t)(served - j);
+                // first pool element this segment has not picked; at most `carried` are skipped
+                int32_t pos = head;
+                for (; pos < M; ++pos) {
+                    const uint16_t c = queue[pos];
+                    bool taken = false;
+                    for (int32_t k = 0; k < carried; ++k) taken = taken || (partner[k] == c);
+                    if (!taken) break;
+                }
+                if (pos == M) pos = M - 1;        // unreachable while R <= N-1; keeps indices in range
+                const uint16_t c = queue[pos];
+                for (int32_t q = pos; q > head; --q) queue[q] = queue[q - 1];   // skipped keep their order
+                ++head;
+                picks[j] = (int32_t)c;
+                ++served;
+            }
+        }
+        __syncthreads();
     }
 }
 
@@ -171,7 +192,7 @@ __global__ __launch_bounds__(1024) void peer_in_degree_kernel(int32_t* __restric
 
 hipError_t launch_peer_table_pooled(int32_t* peers, int32_t N, int32_t S, int32_t R, uint64_t seed,
                                     uint64_t round, hipStream_t st) {
-    const size_t lds = (size_t)(N > 1 ? N - 1 : 1) * sizeof(int32_t);
+    const size_t lds = (size_t)(N > 1 ? N - 1 : 1) * 2 * sizeof(uint16_t);
     hipLaunchKernelGGL(peer_table_pooled_kernel, dim3((uint32_t)N), dim3(64), lds, st, peers, N, S,
                        R, seed, round);
     return hipGetLastError();
