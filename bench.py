@@ -208,6 +208,8 @@ def main():
     ap.add_argument("--shape", default="", help="ad-hoc workload N,P,S,R instead of a named one")
     ap.add_argument("--tiled-cols", type=int, default=0, help="tile width of the tiled layout")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-budget", type=float, default=15.0,
+                    help="seconds of CPU work for the oracle baseline (whole rounds)")
     ap.add_argument("--sweep-paper", action="store_true",
                     help="instead of the benchmark line: the paper's R and S sweeps (30 workers)")
     ap.add_argument("--extras", action="store_true",
@@ -384,7 +386,7 @@ def main():
     if other is not None:
         out["other_layout"] = other
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, X0_host)
+        out["cpu_baseline"] = cpu_baseline(wl, X0_host, args.cpu_budget)
         out["cpu_baseline"]["host_cores_visible"] = os.cpu_count()
     print(json.dumps(out), flush=True)
 
