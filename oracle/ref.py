@@ -22,9 +22,11 @@ _f64p = ctypes.POINTER(ctypes.c_double)
 def lib():
     global _LIB
     if _LIB is None:
-        if not os.path.exists(_build.LIB):
+        # COMBO_REF_LIB: load another build of the oracle (used by the mutation tests)
+        path = os.environ.get("COMBO_REF_LIB") or _build.LIB
+        if path == _build.LIB and not os.path.exists(path):
             _build.build()
-        L = ctypes.CDLL(_build.LIB)
+        L = ctypes.CDLL(path)
         L.combo_ref_segment_bounds.argtypes = [ctypes.c_int64, ctypes.c_int32, _i64p, _i64p]
         L.combo_ref_segment_bounds.restype = ctypes.c_int
         L.combo_ref_mix64.argtypes = [ctypes.c_uint64]

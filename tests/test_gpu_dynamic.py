@@ -118,3 +118,19 @@ def test_all_active_equals_static_round(combo, ref):
     combo.segment_gossip_round_dynamic(b, src, t, st, P, S, R)
     torch.cuda.synchronize()
     assert torch.equal(a.view(torch.int32), b.view(torch.int32))
+
+
+def test_offline_rows_are_copied_even_with_stale_table_entries(combo, ref):
+    N, P, S, R = 6, 10_007, 5, 2
+    Xh = np.random.default_rng(1).normal(0, 1, (N, P)).astype(np.float32)
+    st = np.array([1, 0, 1, 1, 0, 1], np.uint8)
+    T = ref.make_peer_table(N, S, R, 0, 0)
+    want = ref.gossip_round_dynamic(Xh, T, st, P, S, R)
+    for kernel in (0, 1):
+        combo.tune(combo.TUNE_KERNEL, kernel)
+        src = torch.from_numpy(Xh).cuda()
+        dst = torch.zeros_like(src)
+        combo.segment_gossip_round_dynamic(dst, src, torch.from_numpy(T.reshape(-1)).cuda(),
+                                           torch.from_numpy(st).cuda(), P, S, R)
+        torch.cuda.synchronize()
+        assert np.array_equal(dst.cpu().numpy().view(np.uint32), want.view(np.uint32))

@@ -135,3 +135,15 @@ def test_newcomer_with_nobody_to_ask_keeps_its_parameters(ref):
     T = ref.make_peer_table_dynamic(st, 3, 1, 2, 0, 0)
     assert np.all(T == -1)
     assert np.array_equal(ref.gossip_round_dynamic(X, T, st, P=3, S=1, R=2), X)
+
+
+def test_offline_worker_keeps_its_row_whatever_its_table_row_says(ref):
+    """The round goes by the status, not by the table: an offline worker whose table row
+    still holds stale valid entries does not aggregate."""
+    N, P, S, R = 6, 50, 5, 2
+    X = np.random.default_rng(1).normal(0, 1, (N, P)).astype(np.float32)
+    T = ref.make_peer_table(N, S, R, 0, 0)             # every row full of valid entries
+    st = np.array([1, 0, 1, 1, 0, 1], np.uint8)
+    Y = ref.gossip_round_dynamic(X, T, st, P, S, R)
+    assert np.array_equal(Y[[1, 4]], X[[1, 4]])
+    assert not np.array_equal(Y[0], X[0])
