@@ -136,6 +136,20 @@ def extras(combo, wl):
         rec.update(kw)
         print(json.dumps(rec), flush=True)
 
+    # practical ceilings on this device for the same footprint: a plain device-to-device copy
+    # and the library's own round with R = 0 (a copy through the slab kernel), both layouts
+    emit("torch copy_ of one arena half (ceiling probe)", time_kernel(
+        lambda: arena[1].copy_(arena[0]), stream), 8 * N * ld, note="bytes = read + write")
+    emit("round with R=0, row-major (copy through the slab kernel)", time_kernel(
+        lambda: combo.segment_gossip_round(arena[1], arena[0], None, P, S, 0, stream=stream), stream),
+        8 * N * P, note="bytes = read + write")
+    wt0 = combo.tiled_cols(N, R)
+    t0 = torch.zeros((2, combo.tiled_elems(N, P, wt0)), dtype=torch.float32, device="cuda")
+    combo.pack_tiled(t0[0], arena[0], N, P, wt0)
+    emit("round with R=0, tiled (copy through the slab kernel)", time_kernel(
+        lambda: combo.segment_gossip_round_tiled(t0[1], t0[0], wt0, None, N, P, S, 0, stream=stream),
+        stream), 8 * N * P, note="bytes = read + write", tiled_cols=wt0)
+    del t0
     emit("combo_make_peer_table", time_kernel(
         lambda: combo.make_peer_table(peers, N, S, R, 0, 1, stream=stream), stream))
     emit("combo_make_peer_table_pooled", time_kernel(

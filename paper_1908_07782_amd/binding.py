@@ -34,8 +34,14 @@ def lib():
     global _LIB
     if _LIB is None:
         if not os.path.exists(LIB_PATH):
-            raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_1908_07782_amd.build` "
-                              "(there is no fallback path)")
+            # nothing built yet: compile the HIP library now; there is no other code path
+            try:
+                from . import build as _build
+                _build.build()
+            except Exception as e:  # noqa: BLE001
+                raise ImportError(f"{LIB_PATH} is missing and could not be built ({e}); run "
+                                  "`python -m paper_1908_07782_amd.build` - there is no fallback "
+                                  "path") from e
         L = ctypes.CDLL(LIB_PATH)
         vp, i32, i64, u64, f32 = (ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64,
                                   ctypes.c_float)
