@@ -5,8 +5,8 @@
 namespace combo {
 
 size_t slab_lds_bytes(int32_t N, int32_t R, int W) {
-    // slab, peer list, dataset sizes, status
-    return (size_t)N * (size_t)W * 4 + (size_t)N * (size_t)R * 4 + (size_t)N * 4 + (size_t)N * 4;
+    // slab, peer list, dataset sizes, status, swap partners of the in-kernel draw
+    return (size_t)N * (size_t)W * 4 + 2 * (size_t)N * (size_t)R * 4 + (size_t)N * 4 + (size_t)N * 4;
 }
 
 // 256 threads for slabs of up to 768 128-bit words (12 KiB), 512 beyond

@@ -58,6 +58,7 @@ __global__ __launch_bounds__(kSlabThreads) void gossip_slab_kernel(const RoundAr
     int32_t* lds_peers = reinterpret_cast<int32_t*>(lds + total4);     // [N][R]
     float* lds_d = reinterpret_cast<float*>(lds_peers + (size_t)N * (size_t)R);   // [N]
     int32_t* lds_status = reinterpret_cast<int32_t*>(lds_d + N);                  // [N]
+    int32_t* lds_partner = lds_status + N;                                        // [N][R], HASHED
 
     const int64_t col0 = (int64_t)blockIdx.x * W;
     const int64_t col_end = col0 + W < a.P ? col0 + W : a.P;
@@ -98,10 +99,17 @@ __global__ __launch_bounds__(kSlabThreads) void gossip_slab_kernel(const RoundAr
                 }
             }
             if (HASHED && base == 0) {
-                // the slab loads are in flight: draw the peer lists of this strip meanwhile
+                // the slab loads are in flight: draw the peer lists of this strip meanwhile.
+                // One thread per (worker, step) evaluates the hash and the swap partner; after
+                // a barrier one thread per worker turns its R partners into picks.
+                for (int i = threadIdx.x; R > 0 && i < N * R; i += kSlabThreads) {
+                    const int w = i / (R > 0 ? R : 1);
+                    lds_partner[i] = shuffle_partner(a.hash_sr, w, s0, i - w * R, N);
+                }
+                __syncthreads();
                 for (int w = threadIdx.x; w < N; w += kSlabThreads) {
                     int32_t drawn[kMaxHashedR];
-                    draw_peers(a.hash_sr, w, s0, N, R, drawn);
+                    picks_from_partners(lds_partner + w * R, w, R, drawn);
 #pragma unroll
                     for (int j = 0; j < kMaxHashedR; ++j)
                         if (j < R) lds_peers[w * R + j] = drawn[j];

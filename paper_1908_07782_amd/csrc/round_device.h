@@ -78,6 +78,35 @@ constexpr int kMaxHashedR = 8;   // replica counts the in-kernel peer draw suppo
 // Fisher-Yates shuffle of the N-1 other workers, on a virtual array whose displaced
 // slots (at most one per step) are kept in registers.  Same picks, same order as the
 // peer-table kernel.  h_sr = hash state after seed and round.
+// swap partner of shuffle step j for (w, s): j + reduce(hash(seed, round, w, s, j), N-1-j)
+__device__ __forceinline__ int32_t shuffle_partner(uint64_t h_sr, int32_t w, int32_t s, int32_t j,
+                                                   int32_t N) {
+    const uint64_t h = hash_take_in(hash_take_in(h_sr, (uint64_t)w), (uint64_t)s);
+    const uint64_t word = hash_take_in(h, (uint64_t)j);
+    return j + (int32_t)(((word >> 32) * (uint64_t)(uint32_t)(N - 1 - j)) >> 32);
+}
+
+// the picks given the R swap partners (partner[j] for step j): pure integer bookkeeping
+__device__ __forceinline__ void picks_from_partners(const int32_t* partner, int32_t w, int32_t R,
+                                                    int32_t (&out)[kMaxHashedR]) {
+    int32_t pos[kMaxHashedR], val[kMaxHashedR];
+#pragma unroll
+    for (int j = 0; j < kMaxHashedR; ++j) {
+        if (j < R) {
+            const int32_t r = partner[j];
+            int32_t at_r = r, at_j = j;              // current contents of slots r and j
+#pragma unroll
+            for (int k = 0; k < j; ++k) {            // the latest displacement of a slot wins
+                if (pos[k] == r) at_r = val[k];
+                if (pos[k] == j) at_j = val[k];
+            }
+            out[j] = at_r + (at_r >= w ? 1 : 0);     // skip over w itself
+            pos[j] = r;                              // slot r now holds what slot j held
+            val[j] = at_j;
+        }
+    }
+}
+
 __device__ __forceinline__ void draw_peers(uint64_t h_sr, int32_t w, int32_t s, int32_t N, int32_t R,
                                            int32_t (&out)[kMaxHashedR]) {
     const uint64_t h = hash_take_in(hash_take_in(h_sr, (uint64_t)w), (uint64_t)s);
