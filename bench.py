@@ -194,6 +194,34 @@ def extras(combo, wl):
                                                       stream=stream), stream),
             (8 + 4 * tau) * N * P, note="bytes = x read + tau gradient reads + write")
         del grads
+    # the same variants on the tiled arena (the layout the round is timed on by default)
+    del arena
+    t = torch.zeros((2, combo.tiled_elems(N, P, Wt)), dtype=torch.float32, device="cuda")
+    rows = torch.zeros((N, ld), dtype=torch.float32, device="cuda")
+    combo.workloads.fill_params(rows, wl)
+    combo.pack_tiled(t[0], rows, N, P, Wt)
+    del rows
+    emit("combo_segment_gossip_round_tiled", time_kernel(
+        lambda: combo.segment_gossip_round_tiled(t[1], t[0], Wt, peers, N, P, S, R, stream=stream),
+        stream), 8 * N * P, note="bytes = compulsory read + write", tiled_cols=Wt)
+    emit("combo_segment_gossip_round_tiled (dataset-size weights)", time_kernel(
+        lambda: combo.segment_gossip_round_tiled(t[1], t[0], Wt, peers, N, P, S, R, dataset_sizes=dsz,
+                                                 stream=stream), stream), 8 * N * P,
+        note="bytes = compulsory read + write", tiled_cols=Wt)
+    combo.make_peer_table_dynamic(peers, st, N, S, R, 0, 1)
+    emit("combo_segment_gossip_round_tiled (dynamic workers)", time_kernel(
+        lambda: combo.segment_gossip_round_tiled(t[1], t[0], Wt, peers, N, P, S, R, status=st,
+                                                 stream=stream), stream), 8 * N * P,
+        note="bytes = compulsory read + write", tiled_cols=Wt)
+    combo.make_peer_table(peers, N, S, R, 0, 1)
+    for tau in (1, 2):
+        grads = torch.zeros(tau * combo.tiled_elems(N, P, Wt), dtype=torch.float32, device="cuda")
+        grads.normal_(0, 1e-3)
+        emit(f"combo_local_sgd_steps_then_gossip_tiled tau={tau}", time_kernel(
+            lambda: combo.local_sgd_steps_then_gossip_tiled(t[1], t[0], grads, tau, 0.01, Wt, peers,
+                                                            N, P, S, R, stream=stream), stream),
+            (8 + 4 * tau) * N * P, note="bytes = x read + tau gradient reads + write", tiled_cols=Wt)
+        del grads
 
 
 def main():

@@ -371,6 +371,12 @@ int combo_aggregation_divergence_tiled(double* d_dist2, const float* d_x, int32_
     if (need < 0) return (int)need;
     if (d_workspace == nullptr || workspace_bytes < need || ((uintptr_t)d_workspace & 7u) != 0)
         return COMBO_EINVAL;
+    if (combo::divergence_tile_fits(N, tile_cols)) {  // small tiles: one wavefront per tile
+        const hipError_t e = combo::launch_divergence_tiles(d_dist2, (double*)d_workspace, d_x,
+                                                            d_dataset_sizes, N, P, tile_cols,
+                                                            (hipStream_t)stream);
+        return e == hipSuccess ? COMBO_OK : COMBO_EHIP;
+    }
     const hipError_t e = combo::launch_divergence(d_dist2, (double*)d_workspace, d_x, tile_cols,
                                                   d_dataset_sizes, N, P, W, true, tile_cols,
                                                   (hipStream_t)stream);

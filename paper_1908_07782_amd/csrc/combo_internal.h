@@ -54,6 +54,12 @@ bool divergence_width_ok(int32_t N, int strip_cols);
 hipError_t launch_divergence(double* dist2, double* workspace, const float* x, int64_t ld,
                              const float* dsz, int32_t N, int64_t P, int strip_cols, bool vec,
                              int arena_tile, hipStream_t st);
+// tiled arena whose tiles fit the register slots of one wavefront (divergence_tile_fits):
+// one wavefront per tile, no workgroup-level exchange
+bool divergence_tile_fits(int32_t N, int tile_cols);
+hipError_t launch_divergence_tiles(double* dist2, double* workspace, const float* x,
+                                   const float* dsz, int32_t N, int64_t P, int tile_cols,
+                                   hipStream_t st);
 
 // layout conversion kernels (layout.hip)
 hipError_t launch_pack_tiled(float* tiled, const float* rows, int64_t ld, int32_t N, int64_t P,
@@ -67,6 +73,9 @@ int slab_strip_cols(int32_t N, int32_t R, int requested);
 hipError_t launch_round_slab(const RoundArgs& a, int strip_cols, hipStream_t st);
 // the same kernel drawing its peers in-kernel from a.hash_sr (R <= 8, no table)
 hipError_t launch_round_slab_hashed(const RoundArgs& a, int strip_cols, hipStream_t st);
+// dynamic-worker variants (a.status != nullptr); grid and LDS size as computed by launch_round_slab
+hipError_t launch_round_slab_dynamic(const RoundArgs& a, int strip_cols, uint32_t grid, size_t lds,
+                                     hipStream_t st);
 size_t slab_lds_bytes(int32_t N, int32_t R, int strip_cols);
 int slab_threads(int32_t N, int strip_cols);
 

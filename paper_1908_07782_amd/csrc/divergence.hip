@@ -19,6 +19,12 @@
 // with a fixed tree.  No floating-point atomics: the result is reproducible bit for bit.
 //
 // Layouts: row-major [N][ld] and tiled [T][N][Wt] (a strip then spans W/Wt whole tiles).
+//
+// Tiled arenas whose tiles are small enough for the register slots of ONE wavefront
+// (N * Wt/4 <= 512 words, Wt <= 256: every tile of at most 8 KiB) take a second kernel:
+// a wavefront owns whole tiles, its 64 lanes cover 64/(Wt/4) adjacent rows of the tile per
+// slot, so every load instruction reads one contiguous kilobyte, the column sums are
+// complete after the xor-shuffle tree, and the strip loop needs neither LDS nor barriers.
 #include "combo_internal.h"
 #include "round_device.h"
 
@@ -208,6 +214,155 @@ __global__ __launch_bounds__(256) void divergence_reduce_kernel(double* __restri
     if (threadIdx.x == 0) dist2[r] = tree[0];
 }
 
+// ---- one wavefront per tile ------------------------------------------------------------
+
+struct TileDivArgs {
+    double* partial;
+    const float* x;       // tiled arena [T][N][Wt], 16-byte aligned
+    const float* dsz;
+    int64_t P;
+    int32_t N;
+    int32_t Wt;           // tile width: 64, 128 or 256
+    uint64_t ntiles;
+};
+
+// U tiles per pass of a wavefront, kDivSlots / U register slots for the rows of each.
+template <bool WEIGHTED, int U>
+__global__ __launch_bounds__(256) void divergence_tile_kernel(const TileDivArgs a) {
+    extern __shared__ double lds64[];
+    constexpr int SPS = kDivSlots / U;
+    const int N = a.N;
+    const int W4 = a.Wt >> 2;
+    const int w4_shift = 31 - __clz(W4);
+    const int rpp = 64 >> w4_shift;                   // rows covered by one slot of the wavefront
+    double* fold = lds64;                             // [256]
+    float* lds_d = reinterpret_cast<float*>(fold + 256);   // [N]
+    const int t = (int)threadIdx.x;
+    const int lane = t & 63, wave = t >> 6;
+    const int my_c4 = lane & (W4 - 1);
+    const int my_row0 = lane >> w4_shift;
+
+    if (WEIGHTED)
+        for (int i = t; i < N; i += 256) lds_d[i] = a.dsz[i];
+    __syncthreads();
+    double den = 0.0;
+    if (WEIGHTED) { for (int w = 0; w < N; ++w) den += (double)lds_d[w]; }
+    else den = (double)N;
+    const double inv_den = 1.0 / den;
+
+    // slot kk (of every tile of a pass) holds row kk*rpp + my_row0
+    double wt[SPS], acc[SPS];
+#pragma unroll
+    for (int kk = 0; kk < SPS; ++kk) {
+        const int row = kk * rpp + my_row0;
+        wt[kk] = (WEIGHTED && row < N) ? (double)lds_d[row] : 1.0;
+        acc[kk] = 0.0;
+    }
+
+    const uint64_t nwaves = (uint64_t)gridDim.x * 4u;
+    for (uint64_t first = ((uint64_t)blockIdx.x * 4u + (uint64_t)wave) * U; first < a.ntiles;
+         first += nwaves * U) {
+        v4f v[kDivSlots];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint64_t tile = first + (uint64_t)u;
+            const int64_t left = tile < a.ntiles ? a.P - (int64_t)tile * a.Wt : 0;
+            const int width = (int)(left >= a.Wt ? a.Wt : left);   // 0: no such tile
+            const float* base = a.x + (size_t)tile * (size_t)N * (size_t)a.Wt + (size_t)(my_c4 * 4);
+#pragma unroll
+            for (int kk = 0; kk < SPS; ++kk) {
+                const int k = u * SPS + kk;
+                const int row = kk * rpp + my_row0;
+                v[k] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+                if (row < N && width > 0) {
+                    const float* p = base + (size_t)row * (size_t)a.Wt;
+                    if (width == a.Wt) {
+                        v[k] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+                    } else {                          // last tile: zero beyond column P
+                        const int c = my_c4 * 4;
+                        v[k].x = c + 0 < width ? p[0] : 0.0f;
+                        v[k].y = c + 1 < width ? p[1] : 0.0f;
+                        v[k].z = c + 2 < width ? p[2] : 0.0f;
+                        v[k].w = c + 3 < width ? p[3] : 0.0f;
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+#pragma unroll
+            for (int kk = 0; kk < SPS; ++kk) {
+                const int k = u * SPS + kk;
+                if (kk * rpp + my_row0 < N) {
+                    s0 += wt[kk] * (double)v[k].x;
+                    s1 += wt[kk] * (double)v[k].y;
+                    s2 += wt[kk] * (double)v[k].z;
+                    s3 += wt[kk] * (double)v[k].w;
+                }
+            }
+            // lanes that hold the same column group of other rows: fixed xor tree; afterwards
+            // every lane has the complete column sums of its tile
+            for (int off = W4; off < 64; off <<= 1) {
+                s0 += __shfl_xor(s0, off, 64);
+                s1 += __shfl_xor(s1, off, 64);
+                s2 += __shfl_xor(s2, off, 64);
+                s3 += __shfl_xor(s3, off, 64);
+            }
+            const double m0 = s0 * inv_den, m1 = s1 * inv_den, m2 = s2 * inv_den, m3 = s3 * inv_den;
+#pragma unroll
+            for (int kk = 0; kk < SPS; ++kk) {
+                const int k = u * SPS + kk;
+                if (kk * rpp + my_row0 < N) {
+                    // columns beyond P hold zeros and a zero mean: no contribution
+                    const double d0 = (double)v[k].x - m0;
+                    const double d1 = (double)v[k].y - m1;
+                    const double d2 = (double)v[k].z - m2;
+                    const double d3 = (double)v[k].w - m3;
+                    acc[kk] += (d0 * d0 + d1 * d1) + (d2 * d2 + d3 * d3);
+                }
+            }
+        }
+    }
+
+    // fold: row r lives in slot r / rpp, lanes (r % rpp)*W4 .. +W4 of every wavefront; add
+    // them in wavefront order, lane order
+    double row_sum = 0.0;
+#pragma unroll
+    for (int kk = 0; kk < SPS; ++kk) {
+        if (kk * rpp < N) {                           // uniform
+            __syncthreads();
+            fold[t] = acc[kk];
+            __syncthreads();
+            const int g = t - kk * rpp;               // candidate: thread t folds row t
+            if (t < N && g >= 0 && g < rpp)
+                for (int wv = 0; wv < 4; ++wv)
+                    for (int i = 0; i < W4; ++i) row_sum += fold[wv * 64 + g * W4 + i];
+        }
+    }
+    if (t < N) a.partial[(size_t)t * (size_t)gridDim.x + (size_t)blockIdx.x] = row_sum;   // [N][grid]
+}
+
+using TileDivKernel = void (*)(const TileDivArgs);
+
+TileDivKernel tile_kernel_for(bool weighted, int U) {
+    switch (U) {
+        case 8: return weighted ? divergence_tile_kernel<true, 8> : divergence_tile_kernel<false, 8>;
+        case 4: return weighted ? divergence_tile_kernel<true, 4> : divergence_tile_kernel<false, 4>;
+        case 2: return weighted ? divergence_tile_kernel<true, 2> : divergence_tile_kernel<false, 2>;
+        default: return weighted ? divergence_tile_kernel<true, 1> : divergence_tile_kernel<false, 1>;
+    }
+}
+
+// tiles per wavefront pass: as many as the register slots hold
+int tiles_per_pass(int32_t N, int tile_cols) {
+    const int rpp = 64 / (tile_cols / 4);
+    const int slots = (N + rpp - 1) / rpp;            // 1..8 by divergence_tile_fits
+    int pow2 = 1;
+    while (pow2 < slots) pow2 <<= 1;
+    return kDivSlots / pow2;
+}
+
 size_t divergence_lds_bytes(int32_t N, int W, int threads) {
     // two exchange buffers, fold buffer, dataset sizes
     (void)W;
@@ -287,6 +442,49 @@ hipError_t launch_divergence(double* dist2, double* workspace, const float* x, i
         else COMBO_DIV_LAUNCH(false, 512);
     }
 #undef COMBO_DIV_LAUNCH
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(divergence_reduce_kernel, dim3((uint32_t)N), dim3(256), 0, st, dist2, workspace,
+                       grid);
+    return hipGetLastError();
+}
+
+bool divergence_tile_fits(int32_t N, int tile_cols) {
+    return (tile_cols == 64 || tile_cols == 128 || tile_cols == 256) &&
+           (int64_t)N * (tile_cols / 4) <= 64 * kDivSlots;
+}
+
+hipError_t launch_divergence_tiles(double* dist2, double* workspace, const float* x,
+                                   const float* dsz, int32_t N, int64_t P, int tile_cols,
+                                   hipStream_t st) {
+    if (!divergence_tile_fits(N, tile_cols)) return hipErrorInvalidValue;
+    const int U = tiles_per_pass(N, tile_cols);
+    const TileDivKernel kernel = tile_kernel_for(dsz != nullptr, U);
+    const size_t lds = (size_t)256 * 8 + (size_t)N * 4;
+    // persistent grid: the workgroups that are resident at once
+    static int resident[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}};   // [weighted][log2 U]
+    int& res = resident[dsz != nullptr][U == 8 ? 3 : U == 4 ? 2 : U == 2 ? 1 : 0];
+    if (res == 0) {
+        int per_cu = 0, dev = 0, cus = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 256, lds) != hipSuccess ||
+            hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            return hipErrorUnknown;
+        res = per_cu * cus;
+        if (res < 1) res = 256;
+        if (res > 4096) res = 4096;                  // the workspace holds 4096 partials per row
+    }
+    TileDivArgs a;
+    a.partial = workspace;
+    a.x = x;
+    a.dsz = dsz;
+    a.P = P;
+    a.N = N;
+    a.Wt = tile_cols;
+    a.ntiles = ((uint64_t)P + (uint64_t)tile_cols - 1) / (uint64_t)tile_cols;
+    const uint64_t passes = (a.ntiles + (uint64_t)(4 * U) - 1) / (uint64_t)(4 * U);   // per workgroup of 4 wavefronts
+    const uint32_t grid = (uint32_t)(passes < (uint64_t)res ? passes : (uint64_t)res);
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), lds, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(divergence_reduce_kernel, dim3((uint32_t)N), dim3(256), 0, st, dist2, workspace,

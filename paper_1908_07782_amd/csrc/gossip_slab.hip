@@ -5,8 +5,9 @@
 namespace combo {
 
 size_t slab_lds_bytes(int32_t N, int32_t R, int W) {
-    // slab, peer list, dataset sizes, status, swap partners of the in-kernel draw
-    return (size_t)N * (size_t)W * 4 + 2 * (size_t)N * (size_t)R * 4 + (size_t)N * 4 + (size_t)N * 4;
+    // slab, peer list, dataset sizes, status (or denominators), swap partners of the
+    // in-kernel draw, reciprocals of the denominators
+    return (size_t)N * (size_t)W * 4 + 2 * (size_t)N * (size_t)R * 4 + 3 * (size_t)N * 4;
 }
 
 // 256 threads for slabs of up to 768 128-bit words (12 KiB), 512 beyond
@@ -62,26 +63,7 @@ hipError_t launch_round_slab(const RoundArgs& a, int W, hipStream_t st) {
     if (strips > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const size_t lds = slab_lds_bytes(a.N, a.R, W);
     const uint32_t grid = (uint32_t)strips;
-    if (a.status != nullptr) {
-        // dynamic workers: run-time replica loop, no fused step
-        const bool small = slab_threads(a.N, W) == 256;
-        if (a.dsz != nullptr) {
-            if (small)
-                hipLaunchKernelGGL((gossip_slab_kernel<-1, true, false, true, 256>), dim3(grid),
-                                   dim3(256), lds, st, a, W);
-            else
-                hipLaunchKernelGGL((gossip_slab_kernel<-1, true, false, true, 512>), dim3(grid),
-                                   dim3(512), lds, st, a, W);
-        } else {
-            if (small)
-                hipLaunchKernelGGL((gossip_slab_kernel<-1, false, false, true, 256>), dim3(grid),
-                                   dim3(256), lds, st, a, W);
-            else
-                hipLaunchKernelGGL((gossip_slab_kernel<-1, false, false, true, 512>), dim3(grid),
-                                   dim3(512), lds, st, a, W);
-        }
-        return hipGetLastError();
-    }
+    if (a.status != nullptr) return launch_round_slab_dynamic(a, W, grid, lds, st);
     switch (a.R) {
         case 0: return launch_rt<0>(a, W, grid, lds, st);
         case 1: return launch_rt<1>(a, W, grid, lds, st);

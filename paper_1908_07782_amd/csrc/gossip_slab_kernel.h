@@ -59,6 +59,11 @@ __global__ __launch_bounds__(kSlabThreads) void gossip_slab_kernel(const RoundAr
     float* lds_d = reinterpret_cast<float*>(lds_peers + (size_t)N * (size_t)R);   // [N]
     int32_t* lds_status = reinterpret_cast<int32_t*>(lds_d + N);                  // [N]
     int32_t* lds_partner = lds_status + N;                                        // [N][R], HASHED
+    // static weighted rounds keep each row's denominator (the sizes of the worker and its
+    // peers added in list order) and its reciprocal; the slab then holds size * value
+    float* lds_den = reinterpret_cast<float*>(lds_status);                        // [N] (no status then)
+    float* lds_rcp = reinterpret_cast<float*>(lds_partner + (size_t)N * (size_t)R);   // [N]
+    constexpr bool kPrescaled = WEIGHTED && !DYNAMIC;
 
     const int64_t col0 = (int64_t)blockIdx.x * W;
     const int64_t col_end = col0 + W < a.P ? col0 + W : a.P;
@@ -79,7 +84,15 @@ __global__ __launch_bounds__(kSlabThreads) void gossip_slab_kernel(const RoundAr
                 lds_peers[i] = a.peers[((size_t)w * (size_t)a.S + (size_t)s0) * (size_t)R + (size_t)j];
             }
         }
-        if (WEIGHTED)
+        // prescaled rounds: thread w < N adds up row w's denominator; its picks are fetched
+        // ahead of the slab loads so that the dependent size loads need not wait for those
+        int32_t den_pick[RT > 0 ? RT : 1];
+        if (kPrescaled && !HASHED && RT > 0 && (int)threadIdx.x < N) {
+#pragma unroll
+            for (int j = 0; j < (RT > 0 ? RT : 0); ++j)
+                den_pick[j] = a.peers[((size_t)threadIdx.x * (size_t)a.S + (size_t)s0) * (size_t)R + (size_t)j];
+        }
+        if (WEIGHTED && (!kPrescaled || HASHED))
             for (int i = threadIdx.x; i < N; i += kSlabThreads) lds_d[i] = a.dsz[i];
         if (DYNAMIC)
             for (int i = threadIdx.x; i < N; i += kSlabThreads) lds_status[i] = a.status[i];
@@ -87,6 +100,7 @@ __global__ __launch_bounds__(kSlabThreads) void gossip_slab_kernel(const RoundAr
         for (int base = 0; base < total4; base += kSlabThreads * kBatch) {
             v4f x[kBatch], g[kBatch];
             size_t off[kBatch];
+            float d_row[kBatch];
 #pragma unroll
             for (int u = 0; u < kBatch; ++u) {
                 const int idx = base + u * kSlabThreads + (int)threadIdx.x;
@@ -96,6 +110,7 @@ __global__ __launch_bounds__(kSlabThreads) void gossip_slab_kernel(const RoundAr
                     off[u] = (size_t)row * row_stride + strip_base + (size_t)c4 * 4;
                     x[u] = load4_slab(a.src + off[u]);
                     if (FUSED) g[u] = load4_slab(a.grad + off[u]);
+                    if (kPrescaled) d_row[u] = a.dsz[row];
                 }
             }
             if (HASHED && base == 0) {
@@ -113,17 +128,42 @@ __global__ __launch_bounds__(kSlabThreads) void gossip_slab_kernel(const RoundAr
 #pragma unroll
                     for (int j = 0; j < kMaxHashedR; ++j)
                         if (j < R) lds_peers[w * R + j] = drawn[j];
+                    if (kPrescaled) {
+                        float den = lds_d[w];
+#pragma unroll
+                        for (int j = 0; j < kMaxHashedR; ++j)
+                            if (j < R) den = __fadd_rn(den, lds_d[drawn[j]]);
+                        lds_den[w] = den;
+                        lds_rcp[w] = shared_reciprocal(den);
+                    }
+                }
+            }
+            if (kPrescaled && !HASHED && base == 0) {
+                // the slab loads are in flight; the picks fetched ahead have arrived before them
+                for (int w = threadIdx.x; w < N; w += kSlabThreads) {
+                    float den = a.dsz[w];
+                    if (RT > 0 && w == (int)threadIdx.x) {
+#pragma unroll
+                        for (int j = 0; j < (RT > 0 ? RT : 0); ++j) den = __fadd_rn(den, a.dsz[den_pick[j]]);
+                    } else {
+                        const int32_t* pw = a.peers + ((size_t)w * (size_t)a.S + (size_t)s0) * (size_t)R;
+                        for (int j = 0; j < R; ++j) den = __fadd_rn(den, a.dsz[pw[j]]);
+                    }
+                    lds_den[w] = den;
+                    lds_rcp[w] = shared_reciprocal(den);
                 }
             }
             if (FUSED) {
-                // local steps in slice order; the first slice's loads are already in flight
+                // local steps in slice order; the first slice's loads are already in flight, and
+                // the loads of slice t+1 are issued before slice t is applied
                 for (int32_t t = 0; t < a.tau; ++t) {
-                    if (t > 0) {
+                    v4f g_next[kBatch];
+                    if (t + 1 < a.tau) {
 #pragma unroll
                         for (int u = 0; u < kBatch; ++u) {
                             const int idx = base + u * kSlabThreads + (int)threadIdx.x;
                             if (idx < total4)
-                                g[u] = load4_slab(a.grad + (size_t)t * (size_t)a.grad_slice + off[u]);
+                                g_next[u] = load4_slab(a.grad + (size_t)(t + 1) * (size_t)a.grad_slice + off[u]);
                         }
                     }
 #pragma unroll
@@ -131,13 +171,21 @@ __global__ __launch_bounds__(kSlabThreads) void gossip_slab_kernel(const RoundAr
                         const int idx = base + u * kSlabThreads + (int)threadIdx.x;
                         if (idx < total4) x[u] = sgd_step4(x[u], a.lr, g[u]);
                     }
+#pragma unroll
+                    for (int u = 0; u < kBatch; ++u) g[u] = g_next[u];
                 }
             }
 #pragma unroll
             for (int u = 0; u < kBatch; ++u) {
                 const int idx = base + u * kSlabThreads + (int)threadIdx.x;
-                if (idx < total4) slab[idx] = x[u];
+                if (idx < total4) slab[idx] = kPrescaled ? scale4(d_row[u], x[u]) : x[u];
             }
+            // All loads of this pass have been consumed.  Saying so explicitly (vmcnt(0); the
+            // other counters at their maxima, i.e. not waited for) matters: the stores above
+            // sit in per-thread conditionals, so without it the compiler must assume at the
+            // loop's back edge that loads into the same registers may still be pending, and it
+            // then puts a wait in front of every load of the pass, which serialises them.
+            __builtin_amdgcn_s_waitcnt(0x0F70);
         }
         __syncthreads();
 
@@ -158,10 +206,13 @@ __global__ __launch_bounds__(kSlabThreads) void gossip_slab_kernel(const RoundAr
                     cnt = 1;
                 }
                 if (st != 0) {
-                    for (int j = 0; j < R; ++j) {
+#pragma unroll
+                    for (int j = 0; j < (RT >= 0 ? RT : R); ++j) {
                         const int p = pl[j];
+                        // read unconditionally (own row for an unused slot) so that the LDS
+                        // reads of all slots can be issued together; use only valid ones
+                        v4f v = slab[((p < 0 ? w : p) << w4_shift) + c4];
                         if (p < 0) continue;
-                        v4f v = slab[(p << w4_shift) + c4];
                         if (WEIGHTED) {
                             const float dp = lds_d[p];
                             v = scale4(dp, v);
@@ -183,15 +234,15 @@ __global__ __launch_bounds__(kSlabThreads) void gossip_slab_kernel(const RoundAr
                 }
                 y = scale4(a.inv, acc);
             } else {
-                float den = lds_d[w];
-                acc = scale4(den, acc);
-                for (int j = 0; j < R; ++j) {
-                    const int p = pl[j];
-                    const float dp = lds_d[p];
-                    den = __fadd_rn(den, dp);
-                    acc = add4(acc, scale4(dp, slab[(p << w4_shift) + c4]));
+                // the slab holds size * value: add in list order, divide by the row's denominator
+                if (RT >= 0) {
+#pragma unroll
+                    for (int j = 0; j < (RT >= 0 ? RT : 0); ++j)
+                        acc = add4(acc, slab[(pl[j] << w4_shift) + c4]);
+                } else {
+                    for (int j = 0; j < R; ++j) acc = add4(acc, slab[(pl[j] << w4_shift) + c4]);
                 }
-                y = div4(acc, den);
+                y = div4_shared(acc, lds_den[w], lds_rcp[w]);
             }
             store4_stream(a.dst + (size_t)w * row_stride + strip_base + (size_t)c4 * 4, y);
         }

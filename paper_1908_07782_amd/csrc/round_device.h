@@ -46,14 +46,49 @@ __device__ __forceinline__ v4f scale4(float s, v4f a) {
     return y;
 }
 
-__device__ __forceinline__ v4f div4(v4f a, float d) {
+// Quotients by a shared denominator.  Given r = fl(1/d), a / d is obtained, correctly
+// rounded, with one multiply and two fused multiply-adds instead of a division: the
+// product q0 = fl(a*r) is within one ulp of the quotient, the residual a - q0*d is exact
+// in one fma, and fl(q0 + residual*r) is the correctly rounded quotient (Markstein's
+// division theorem) as long as nothing under- or overflows on the way.  That holds for d
+// and |a| in [2^-60, 2^60]; a zero numerator gives a zero of the numerator's sign.
+// Everything else takes the division instruction sequence.
+constexpr uint32_t kDivLoBits = 0x21800000u;   // 2^-60
+constexpr uint32_t kDivHiBits = 0x5d800000u;   // 2^60
+
+// fl(1/d) if d is in the range of the shortcut, else 0 ("use the division")
+__device__ __forceinline__ float shared_reciprocal(float d) {
+    return (d >= 0x1p-60f && d <= 0x1p60f) ? __fdiv_rn(1.0f, d) : 0.0f;
+}
+
+__device__ __forceinline__ float quotient_by_reciprocal(float a, float d, float r) {
+    const float q0 = __fmul_rn(a, r);
+    const float q1 = __fmaf_rn(__fmaf_rn(-q0, d, a), r, q0);
+    return __builtin_copysignf(q1, a);           // only matters for a == -0
+}
+
+// the four quotients of one 128-bit word by the same denominator; r = shared_reciprocal(d)
+__device__ __forceinline__ v4f div4_shared(v4f a, float d, float r) {
+    const uint32_t ux = __float_as_uint(a.x) & 0x7fffffffu, uy = __float_as_uint(a.y) & 0x7fffffffu;
+    const uint32_t uz = __float_as_uint(a.z) & 0x7fffffffu, uw = __float_as_uint(a.w) & 0x7fffffffu;
+    const uint32_t hi = max(max(ux, uy), max(uz, uw));                  // NaN and inf are the largest
+    const uint32_t lo = min(min(ux - 1u, uy - 1u), min(uz - 1u, uw - 1u));   // zero wraps to the top
     v4f y;
-    y.x = __fdiv_rn(a.x, d);
-    y.y = __fdiv_rn(a.y, d);
-    y.z = __fdiv_rn(a.z, d);
-    y.w = __fdiv_rn(a.w, d);
+    if (r != 0.0f && hi <= kDivHiBits && lo >= kDivLoBits - 1u) {
+        y.x = quotient_by_reciprocal(a.x, d, r);
+        y.y = quotient_by_reciprocal(a.y, d, r);
+        y.z = quotient_by_reciprocal(a.z, d, r);
+        y.w = quotient_by_reciprocal(a.w, d, r);
+    } else {
+        y.x = __fdiv_rn(a.x, d);
+        y.y = __fdiv_rn(a.y, d);
+        y.z = __fdiv_rn(a.z, d);
+        y.w = __fdiv_rn(a.w, d);
+    }
     return y;
 }
+
+__device__ __forceinline__ v4f div4(v4f a, float d) { return div4_shared(a, d, shared_reciprocal(d)); }
 
 // ---- the counter-based peer hash (see combo_make_peer_table in the header) ------------
 constexpr uint64_t kHashGamma = 0x9E3779B97F4A7C15ull;   // SplitMix64 increment

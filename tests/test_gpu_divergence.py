@@ -46,7 +46,12 @@ def test_divergence_matches_oracle(combo, ref, N, P, weighted):
 
 
 @pytest.mark.parametrize("N,P,Wt", [(4, 65_536, 512), (32, 200_003, 64), (16, 100_000, 128),
-                                    (100, 50_003, 64), (5, 1_000, 256), (256, 5_000, 64)])
+                                    (100, 50_003, 64), (5, 1_000, 256), (256, 5_000, 64),
+                                    # 8, 4 and 2 tiles per strip, ragged row counts, very wide tiles,
+                                    # and fewer rows than one pass of the workgroup covers
+                                    (16, 70_001, 64), (30, 123_457, 64), (48, 33_333, 64), (8, 99_999, 256),
+                                    (2, 9_999, 512), (3, 7_777, 512), (8, 50_000, 64), (64, 20_000, 64),
+                                    (17, 64 * 4 * 9, 64), (32, 11_689_512 // 16, 64)])
 @pytest.mark.parametrize("weighted", [False, True])
 def test_divergence_tiled_matches_oracle(combo, ref, N, P, Wt, weighted):
     rng = np.random.default_rng(N + P)

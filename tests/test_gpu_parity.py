@@ -483,3 +483,77 @@ def test_rounds_can_be_captured_in_a_hip_graph(combo, ref):
     for k in range(8):
         X = ref.gossip_round(X, ref.make_peer_table(N, S, R, 3, k % 2), P, S, R)
     assert_params_match(eA[:, :P].cpu().numpy(), X, "graph chain")
+
+
+# ------------------------------------------------------- special values, bit for bit
+def _special_matrix(N, P, seed):
+    """Ordinary parameters with a third of the entries replaced by signed zeros, subnormal,
+    tiny, huge, infinite and NaN values: every branch of the weighted quotient."""
+    rng = np.random.default_rng(seed)
+    X = rng.normal(0, 0.05, (N, P)).astype(np.float32)
+    specials = np.array([0.0, -0.0, 1e-45, -1e-45, 1e-40, -3e-39, 1.2e-38, -1.2e-38, 1e-30, -1e-25,
+                         2.0 ** -61, 2.0 ** -60, -2.0 ** -59, 1e-19, 2.0 ** 59, -2.0 ** 60, 2.0 ** 61,
+                         1e19, -1e25, 1e30, -3e38, 3.4e38, np.inf, -np.inf, np.nan], dtype=np.float32)
+    mask = rng.random((N, P)) < 0.33
+    X[mask] = rng.choice(specials, size=int(mask.sum()))
+    # whole columns of one special value, so that sums of only zeros (of either sign), only
+    # subnormals, only huge values occur too
+    cols = np.flatnonzero(rng.random(P) < 0.1)
+    X[:, cols] = rng.choice(specials, size=cols.size)[None, :]
+    return X
+
+
+def _assert_same_bits_or_both_nan(got, want, what):
+    nan_g, nan_w = np.isnan(got), np.isnan(want)
+    assert np.array_equal(nan_g, nan_w), f"{what}: NaN positions differ"
+    same = (got.view(np.uint32) == want.view(np.uint32)) | nan_w
+    assert same.all(), f"{what}: {int((~same).sum())} elements differ, first at {np.argwhere(~same)[0]}"
+
+
+@pytest.mark.parametrize("layout", ["rows", "tiled"])
+@pytest.mark.parametrize("mode", ["plain", "weighted", "weighted_tiny_sizes", "weighted_huge_sizes",
+                                  "dynamic", "dynamic_weighted"])
+def test_special_values_bit_exact(combo, ref, layout, mode):
+    N, P, S, R = 12, 40_003, 5, 3
+    Xh = _special_matrix(N, P, 5)
+    ld = combo.workloads.row_pitch(P)
+    rows = torch.zeros((2, N, ld), dtype=torch.float32, device="cuda")
+    rows[0, :, :P] = torch.from_numpy(Xh).cuda()
+    d = None
+    if "weighted" in mode:
+        d = combo.workloads.dataset_sizes(N, 3, "cuda")
+        if mode == "weighted_tiny_sizes":
+            d = d * 1e-24            # denominators below 2^-60
+        if mode == "weighted_huge_sizes":
+            d = d * 1e17             # denominators above 2^60 for the larger sums
+    status = None
+    if mode.startswith("dynamic"):
+        sh = np.ones(N, dtype=np.uint8)
+        sh[3] = 0
+        sh[7] = 2
+        status = torch.from_numpy(sh).cuda()
+        peers = torch.empty(N * S * R, dtype=torch.int32, device="cuda")
+        combo.make_peer_table_dynamic(peers, status, N, S, R, 9, 2)
+        ph = ref.make_peer_table_dynamic(sh, N, S, R, 9, 2)
+    else:
+        peers = device_table(combo, N, S, R, 9, 2)
+        ph = ref.make_peer_table(N, S, R, 9, 2)
+    dh = None if d is None else d.cpu().numpy()
+    with np.errstate(all="ignore"):
+        if status is None:
+            want = ref.gossip_round(Xh, ph, P, S, R, d=dh)
+        else:
+            want = ref.gossip_round_dynamic(Xh, ph, sh, P, S, R, d=dh)
+    if layout == "rows":
+        if status is None:
+            combo.segment_gossip_round(rows[1], rows[0], peers, P, S, R, dataset_sizes=d)
+        else:
+            combo.segment_gossip_round_dynamic(rows[1], rows[0], peers, status, P, S, R, dataset_sizes=d)
+    else:
+        Wt = combo.tiled_cols(N, R)
+        t = torch.zeros((2, combo.tiled_elems(N, P, Wt)), dtype=torch.float32, device="cuda")
+        combo.pack_tiled(t[0], rows[0], N, P, Wt)
+        combo.segment_gossip_round_tiled(t[1], t[0], Wt, peers, N, P, S, R, dataset_sizes=d, status=status)
+        combo.unpack_tiled(rows[1], t[1], N, P, Wt)
+    torch.cuda.synchronize()
+    _assert_same_bits_or_both_nan(rows[1, :, :P].cpu().numpy(), want, f"{layout} {mode}")
