@@ -201,6 +201,12 @@ def extras(combo, wl):
     combo.workloads.fill_params(rows, wl)
     combo.pack_tiled(t[0], rows, N, P, Wt)
     del rows
+    rows2 = torch.zeros((N, ld), dtype=torch.float32, device="cuda")
+    emit("combo_pack_tiled", time_kernel(lambda: combo.pack_tiled(t[1], rows2, N, P, Wt, stream=stream), stream),
+         8 * N * P, note="bytes = read + write", tiled_cols=Wt)
+    emit("combo_unpack_tiled", time_kernel(lambda: combo.unpack_tiled(rows2, t[0], N, P, Wt, stream=stream), stream),
+         8 * N * P, note="bytes = read + write", tiled_cols=Wt)
+    del rows2
     emit("combo_segment_gossip_round_tiled", time_kernel(
         lambda: combo.segment_gossip_round_tiled(t[1], t[0], Wt, peers, N, P, S, R, stream=stream),
         stream), 8 * N * P, note="bytes = compulsory read + write", tiled_cols=Wt)

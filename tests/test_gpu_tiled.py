@@ -59,6 +59,30 @@ def test_pack_and_unpack_match_numpy(combo, N, P, Wt):
     assert np.array_equal(np_unpack(want, N, P, Wt), Xh)
 
 
+@pytest.mark.parametrize("ld_extra,offset", [(1, 0), (0, 1), (3, 2), (4, 4)])
+def test_pack_and_unpack_any_pitch_and_alignment(combo, ld_extra, offset):
+    """Row pitches that are not multiples of four and base pointers off the 16-byte grid take
+    the scalar conversion; (4, 4) is aligned again and takes the 128-bit one."""
+    N, P, Wt = 6, 3_003, 64
+    Xh = np.random.default_rng(1).normal(0, 1, (N, P)).astype(np.float32)
+    ld = 3_008 + ld_extra
+    raw = torch.full((N * ld + offset + 4,), float("nan"), dtype=torch.float32, device="cuda")
+    rows = raw[offset:offset + N * ld].view(N, ld)
+    rows[:, :P] = torch.from_numpy(Xh).cuda()
+    tiled = torch.full((combo.tiled_elems(N, P, Wt),), float("nan"), dtype=torch.float32, device="cuda")
+    combo.pack_tiled(tiled, rows, N, P, Wt)
+    want = np_pack(Xh, Wt)
+    got = tiled.cpu().numpy()
+    assert np.array_equal(np.isnan(got), np.isnan(want))
+    assert np.array_equal(got[~np.isnan(want)], want[~np.isnan(want)])
+    raw2 = torch.full_like(raw, float("nan"))
+    back = raw2[offset:offset + N * ld].view(N, ld)
+    combo.unpack_tiled(back, tiled, N, P, Wt)
+    torch.cuda.synchronize()
+    assert np.array_equal(back[:, :P].cpu().numpy(), Xh) and bool(torch.isnan(back[:, P:]).all())
+    assert bool(torch.isnan(raw2[:offset]).all()) and bool(torch.isnan(raw2[offset + N * ld:]).all())
+
+
 ROUND_CASES = [
     # N, P, S, R, Wt
     (4, 65_536, 8, 2, 512), (5, 10_007, 7, 3, 64), (8, 40_001, 3, 4, 128), (32, 9_999, 32, 4, 64),
