@@ -126,6 +126,81 @@ __global__ __launch_bounds__(64) void peer_table_pooled_kernel(int32_t* __restri
     }
 }
 
+// The same selection for N <= 65, where one permutation fits the wavefront: lane l holds
+// queue element l, so the queue, the swap partners and the current segment's picks live in
+// registers (c2's 4096 entries: 45 us with the LDS kernel above).
+//   - Shuffle: every lane tracks where ITS element goes while the swaps are replayed (one
+//     cross-lane read of the partner per step), then one forward permute places the elements.
+//   - Serving: only the segment that straddles the refill can meet a pick it already has, and
+//     it always completes within the new permutation (it lacks at most R-1 <= M-1 picks and
+//     only its own earlier picks are skipped).  Those few requests go one by one (ballot for
+//     the first lane holding a candidate the segment does not have yet; skipped elements move
+//     up one lane).  After that no request of this permutation can collide, so the rest of the
+//     queue is handed out in order with ONE coalesced store.
+__global__ __launch_bounds__(64) void peer_table_pooled_wave_kernel(int32_t* __restrict__ peers,
+                                                                    int32_t N, int32_t S, int32_t R,
+                                                                    uint64_t seed, uint64_t round) {
+    const int32_t M = N - 1;                      // 1..64 candidates
+    const int32_t w = (int32_t)blockIdx.x;
+    const int lane = (int)threadIdx.x;
+    uint64_t hw = finalise((seed ^ kPoolTag) + kGamma);
+    hw = take_in(hw, round);
+    hw = take_in(hw, (uint64_t)w);
+
+    const int64_t requests = (int64_t)S * R;
+    int32_t* out = peers + (size_t)w * (size_t)S * (size_t)R;
+    int64_t served = 0;
+    int32_t j = 0;                                // position of the next request in its segment
+    int32_t cpick = -1;                           // lane k: k-th pick of the segment in progress
+    for (int64_t epoch = 0; served < requests; ++epoch) {
+        const uint64_t he = take_in(hw, (uint64_t)epoch);
+        int32_t partner = lane;
+        if (lane < M) {
+            const uint64_t word = take_in(he, (uint64_t)lane);
+            partner = lane + (int32_t)(((word >> 32) * (uint64_t)(uint32_t)(M - lane)) >> 32);
+        }
+        int32_t where = lane;                     // position of the element that starts in this lane
+        for (int32_t i = 0; i + 1 < M; ++i) {     // full Fisher-Yates: step i swaps positions i and r
+            const int32_t r = __builtin_amdgcn_readlane(partner, i);
+            where = where == i ? r : (where == r ? i : where);
+        }
+        // lane l sends its element (identity order, skipping w) to lane where[l]
+        int32_t q = __builtin_amdgcn_ds_permute(where << 2, lane + (lane >= w ? 1 : 0));
+
+        int32_t head = 0;                         // lanes head..M-1 are still in the pool
+        // the straddling segment: its first j picks (cpick lanes 0..j-1) came from earlier permutations
+        const int32_t carried = j;
+        while (j != 0 && head < M && served < requests) {
+            bool is_free = lane >= head && lane < M;
+            for (int32_t k = 0; k < carried; ++k)
+                is_free = is_free && q != __builtin_amdgcn_readlane(cpick, k);
+            const uint64_t mask = __ballot(is_free);
+            // never empty while R <= N-1; the fallback keeps the lane index in range
+            const int32_t pos = mask != 0 ? (int32_t)__ffsll((unsigned long long)mask) - 1 : M - 1;
+            const int32_t c = __builtin_amdgcn_readlane(q, pos);
+            if (pos != head) {                    // skipped elements keep their order
+                const int32_t below = __shfl_up(q, 1, 64);
+                if (lane > head && lane <= pos) q = below;
+            }
+            ++head;
+            if (lane == j) cpick = c;
+            if (lane == 0) out[served] = c;
+            ++served;
+            if (++j == R) j = 0;
+        }
+        if (j == 0) {                             // always, while R <= N-1
+            // the rest of the queue goes out in order
+            const int64_t left = requests - served;
+            const int32_t count = (int32_t)(left < (int64_t)(M - head) ? left : (int64_t)(M - head));
+            if (lane >= head && lane < head + count) out[served + (lane - head)] = q;
+            served += count;
+            j = count % R;
+            // picks of the segment now in progress: the last j elements handed out
+            cpick = __shfl(q, head + count - j + lane, 64);
+        }
+    }
+}
+
 // Selection with dynamic workers (Sec. 4.2): candidates are the ACTIVE others (offline
 // workers are not asked, newcomers are not yet known to anyone); an offline requester
 // asks nobody.  One wavefront per (w, s): the lanes compact the candidate list into LDS
@@ -192,6 +267,11 @@ __global__ __launch_bounds__(1024) void peer_in_degree_kernel(int32_t* __restric
 
 hipError_t launch_peer_table_pooled(int32_t* peers, int32_t N, int32_t S, int32_t R, uint64_t seed,
                                     uint64_t round, hipStream_t st) {
+    if (N - 1 <= 64 && R <= 64) {                 // one permutation per wavefront, all in registers
+        hipLaunchKernelGGL(peer_table_pooled_wave_kernel, dim3((uint32_t)N), dim3(64), 0, st, peers, N,
+                           S, R, seed, round);
+        return hipGetLastError();
+    }
     const size_t lds = (size_t)(N > 1 ? N - 1 : 1) * 2 * sizeof(uint16_t);
     hipLaunchKernelGGL(peer_table_pooled_kernel, dim3((uint32_t)N), dim3(64), lds, st, peers, N, S,
                        R, seed, round);

@@ -17,7 +17,11 @@ def combo():
 
 CASES = [(30, 10, 2, 0, 0), (4, 8, 2, 0, 0), (32, 32, 4, 0, 3), (32, 10, 2, 7, 9), (100, 7, 3, 5, 19),
          (16, 16, 4, 0, 4), (5, 9, 4, 1, 1), (2, 3, 1, 0, 0), (7, 3, 6, 2, 2), (100, 3, 99, 1, 0),
-         (1000, 2, 5, 2**63 + 1, 2**33), (3, 200, 2, 8, 8)]
+         (1000, 2, 5, 2**63 + 1, 2**33), (3, 200, 2, 8, 8),
+         # around the limit of the register-resident kernel (64 candidates), R up to N-1 there,
+         # segments that straddle many refills
+         (65, 5, 64, 3, 1), (65, 7, 3, 0, 2), (66, 7, 3, 0, 2), (64, 9, 63, 4, 4), (33, 17, 5, 6, 6),
+         (17, 40, 16, 1, 3), (2, 50, 1, 9, 9), (48, 64, 7, 2**40, 5), (9, 11, 8, 0, 1)]
 
 
 @pytest.mark.parametrize("N,S,R,seed,rnd", CASES)
