@@ -557,3 +557,40 @@ def test_special_values_bit_exact(combo, ref, layout, mode):
         combo.unpack_tiled(rows[1], t[1], N, P, Wt)
     torch.cuda.synchronize()
     _assert_same_bits_or_both_nan(rows[1, :, :P].cpu().numpy(), want, f"{layout} {mode}")
+
+
+@pytest.mark.parametrize("layout", ["rows", "tiled"])
+@pytest.mark.parametrize("sizes", [(1.0, 1.0), (3.0, 5.0), (1e3, 7e3), (0.1, 0.2), (2.0 ** -31, 2.0 ** -31),
+                                   (2.0 ** 58, 2.0 ** 58), (2.0 ** 59, 2.0 ** 59), (2.0 ** -61, 2.0 ** -62),
+                                   (float(np.float32(1.9999999)), 0.0), (float(np.float32(1.0000001)), 0.0),
+                                   (1e-30, 3e-30), (12345.0, 0.0)])
+def test_weighted_quotient_on_random_bit_patterns(combo, ref, layout, sizes):
+    """Two workers that average each other with dataset sizes (d0, d1): every output is
+    fl(fl(d0*x0 + d1*x1) / fl(d0 + d1)).  Numerators are arbitrary finite bit patterns, the
+    denominators cover both sides of the range in which the kernel replaces the division by
+    a multiplication with the shared reciprocal plus a residual correction."""
+    N, P, S, R = 2, 300_001, 1, 1
+    rng = np.random.default_rng(int(abs(hash(sizes)) % 2**31))
+    bits = rng.integers(0, 2**32, size=(N, P), dtype=np.uint64).astype(np.uint32)
+    Xh = bits.view(np.float32).copy()
+    Xh[~np.isfinite(Xh)] = 0.0
+    Xh[1, ::3] = 0.0                          # a third of the outputs are d0*x0 / (d0+d1) exactly
+    dh = np.array(sizes, dtype=np.float32)
+    ph = ref.make_peer_table(N, S, R, 0, 0)   # with two workers each one's only peer is the other
+    with np.errstate(all="ignore"):
+        want = ref.gossip_round(Xh, ph, P, S, R, d=dh)
+    ld = combo.workloads.row_pitch(P)
+    rows = torch.zeros((2, N, ld), dtype=torch.float32, device="cuda")
+    rows[0, :, :P] = torch.from_numpy(Xh).cuda()
+    peers = torch.from_numpy(ph.reshape(-1).astype(np.int32)).cuda()
+    d = torch.from_numpy(dh).cuda()
+    if layout == "rows":
+        combo.segment_gossip_round(rows[1], rows[0], peers, P, S, R, dataset_sizes=d)
+    else:
+        Wt = combo.tiled_cols(N, R)
+        t = torch.zeros((2, combo.tiled_elems(N, P, Wt)), dtype=torch.float32, device="cuda")
+        combo.pack_tiled(t[0], rows[0], N, P, Wt)
+        combo.segment_gossip_round_tiled(t[1], t[0], Wt, peers, N, P, S, R, dataset_sizes=d)
+        combo.unpack_tiled(rows[1], t[1], N, P, Wt)
+    torch.cuda.synchronize()
+    _assert_same_bits_or_both_nan(rows[1, :, :P].cpu().numpy(), want, f"{layout} sizes {sizes}")
