@@ -51,7 +51,10 @@ def test_divergence_matches_oracle(combo, ref, N, P, weighted):
                                     # and fewer rows than one pass of the workgroup covers
                                     (16, 70_001, 64), (30, 123_457, 64), (48, 33_333, 64), (8, 99_999, 256),
                                     (2, 9_999, 512), (3, 7_777, 512), (8, 50_000, 64), (64, 20_000, 64),
-                                    (17, 64 * 4 * 9, 64), (32, 11_689_512 // 16, 64)])
+                                    (17, 64 * 4 * 9, 64), (32, 11_689_512 // 16, 64),
+                                    # tiles larger than one wavefront's register slots (workgroup kernel), odd row counts
+                                    (33, 4_000, 64), (65, 7_000, 64), (128, 9_999, 64), (129, 3_000, 64),
+                                    (40, 5_000, 128), (20, 6_001, 256), (100, 1_000_003 // 4, 64)])
 @pytest.mark.parametrize("weighted", [False, True])
 def test_divergence_tiled_matches_oracle(combo, ref, N, P, Wt, weighted):
     rng = np.random.default_rng(N + P)
