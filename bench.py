@@ -89,31 +89,52 @@ def time_kernel(fn, stream, reps=20, warm=3):
     return a.elapsed_time(b) / reps
 
 
-def sweep_paper(combo, P):
+def sweep_paper(combo, P, layout="rows"):
     """The paper's own sweeps as bandwidth curves (Sec. 5.2: 30 workers; R = 1..16 at
     S = 10; S = 1..10 at R = 2).  One JSON line per point."""
     import torch
     N = 30
     ld = combo.workloads.row_pitch(P)
     wl = combo.workloads.small_case(N, P, 10, 2, scale=0.02)
-    arena = torch.zeros((2, N, ld), dtype=torch.float32, device="cuda")
-    combo.workloads.fill_params(arena[0], wl)
+    rows = torch.zeros((N, ld), dtype=torch.float32, device="cuda")
+    combo.workloads.fill_params(rows, wl)
     stream = torch.cuda.current_stream()
     points = [("R", 10, r) for r in (1, 2, 3, 4, 6, 8, 12, 16, 29)] + \
              [("S", s, 2) for s in (1, 2, 3, 4, 6, 8, 10)]
     ws = torch.empty(combo.aggregation_divergence_workspace(N, P) // 8, dtype=torch.float64, device="cuda")
     d2 = torch.empty(N, dtype=torch.float64, device="cuda")
-    combo.aggregation_divergence(d2, arena[0], P, ws, stream=stream)
-    rho0 = float(d2.max().sqrt())
+    tiled = layout == "tiled"
+    if tiled:
+        Wt = combo.tiled_cols(N, 2)
+        arena = torch.zeros((2, combo.tiled_elems(N, P, Wt)), dtype=torch.float32, device="cuda")
+        combo.pack_tiled(arena[0], rows, N, P, Wt)
+        del rows
+
+        def one_round(peers, S, R):
+            combo.segment_gossip_round_tiled(arena[1], arena[0], Wt, peers, N, P, S, R, stream=stream)
+
+        def rho_of(x):
+            combo.aggregation_divergence_tiled(d2, x, Wt, N, P, ws, stream=stream)
+            return float(d2.max().sqrt())
+    else:
+        arena = torch.zeros((2, N, ld), dtype=torch.float32, device="cuda")
+        arena[0].copy_(rows)
+        del rows
+
+        def one_round(peers, S, R):
+            combo.segment_gossip_round(arena[1], arena[0], peers, P, S, R, stream=stream)
+
+        def rho_of(x):
+            combo.aggregation_divergence(d2, x, P, ws, stream=stream)
+            return float(d2.max().sqrt())
+    rho0 = rho_of(arena[0])
     for which, S, R in points:
         peers = torch.empty(N * S * R, dtype=torch.int32, device="cuda")
         combo.make_peer_table(peers, N, S, R, 0, 0)
-        ms = time_kernel(lambda: combo.segment_gossip_round(arena[1], arena[0], peers, P, S, R,
-                                                            stream=stream), stream)
+        ms = time_kernel(lambda: one_round(peers, S, R), stream)
         # aggregation divergence (Sec. 4.3, Def. 2) after this one round from independent models
-        combo.aggregation_divergence(d2, arena[1], P, ws, stream=stream)
-        rho = float(d2.max().sqrt())
-        print(json.dumps({"sweep": which, "N": N, "P": P, "S": S, "R": R, "kernel_ms": ms,
+        rho = rho_of(arena[1])
+        print(json.dumps({"sweep": which, "layout": layout, "N": N, "P": P, "S": S, "R": R, "kernel_ms": ms,
                           "rounds_per_s": 1e3 / ms,
                           "effective_GBs": 4 * (R + 2) * N * P / ms / 1e6,
                           "compulsory_GBs": 8 * N * P / ms / 1e6,
@@ -292,7 +313,7 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     if args.sweep_paper:
-        return sweep_paper(combo, wl.P)
+        return sweep_paper(combo, wl.P, args.layout)
     if args.extras:
         return extras(combo, wl)
 
