@@ -199,8 +199,10 @@ int combo_segment_gossip_round_dynamic(float* d_dst, const float* d_src, int64_t
  * padding: never read, never written.  Element-wise work (the local SGD step) is
  * layout-agnostic, so a simulation can live in this layout and unpack only to export.
  *
- *   combo_tiled_cols(N, R)          recommended Wt (a power of two in [64, 1024]), or a
- *                                   negative status if N rows of 64 columns do not fit in LDS
+ *   combo_tiled_cols(N, R)          recommended Wt (a power of two in [8, 1024]: 8 KiB tiles
+ *                                   for N <= 32, then the widest of 64, 32, 16, 8 columns
+ *                                   whose tile stays within 32 KiB), or a negative status if
+ *                                   N rows of 8 columns do not fit in LDS (N > about 1500)
  *   combo_tiled_elems(N, P, Wt)     floats in one tiled matrix, = T*N*Wt
  *   combo_pack_tiled / combo_unpack_tiled   convert row-major <-> tiled (pure copies)
  *   combo_segment_gossip_round_tiled        the round of combo_segment_gossip_round on
@@ -212,7 +214,7 @@ int combo_segment_gossip_round_dynamic(float* d_dst, const float* d_src, int64_t
  *                                   modified (the steps are folded into the slab fill)
  * Same arithmetic, order and results as the row-major entry points, bit for bit.
  * Errors: COMBO_EINVAL for bad sizes, NULL or not 16-byte aligned buffers, Wt not a power
- * of two in [64, 1024]; COMBO_EALIAS for overlapping buffers; COMBO_ERANGE when the N x Wt
+ * of two in [8, 1024]; COMBO_EALIAS for overlapping buffers; COMBO_ERANGE when the N x Wt
  * slab with its peer list does not fit in 64 KiB of LDS.
  */
 int32_t combo_tiled_cols(int32_t N, int32_t R);
@@ -265,7 +267,7 @@ int combo_round_hashed(float* d_dst, const float* d_src, const float* d_grads, i
  *                before and after the call
  * combo_aggregation_divergence_tiled reads a tiled matrix [T][N][tile_cols] instead.
  * Errors: COMBO_EINVAL for bad sizes, NULL pointers, a workspace that is too small or
- * misaligned; COMBO_ERANGE for N > 256, or when N rows of a tile exceed the kernel's
+ * misaligned; COMBO_ERANGE for N > 512, or when N rows of a tile exceed the kernel's
  * register slots (N * tile_cols > 16384).
  * combo_aggregation_divergence_workspace returns the byte count (4096*N*8), or a negative
  * status.

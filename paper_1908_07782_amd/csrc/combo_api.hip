@@ -216,7 +216,7 @@ int combo_local_sgd_then_gossip(float* d_dst, float* d_src, const float* d_grad,
 namespace {
 
 bool tile_cols_ok(int tile_cols) {
-    return tile_cols >= 64 && tile_cols <= 1024 && (tile_cols & (tile_cols - 1)) == 0;
+    return tile_cols >= 8 && tile_cols <= 1024 && (tile_cols & (tile_cols - 1)) == 0;
 }
 
 int64_t tiled_elems(int32_t N, int64_t P, int tile_cols) {
@@ -247,10 +247,15 @@ int64_t combo_tiled_elems(int32_t N, int64_t P, int32_t tile_cols) {
 
 int32_t combo_tiled_cols(int32_t N, int32_t R) {
     if (N < 1 || R < 0) return COMBO_EINVAL;
-    // 8 KiB slabs measured best; never below 64 columns (256-byte row chunks)
+    // 8 KiB slabs measured best while a row chunk has at least 64 columns (N <= 32); for
+    // more workers keep the chunk as wide as a slab of at most 32 KiB allows (64 columns up
+    // to N = 128, 32 up to 256, 16 up to 512, then 8): a tile is one contiguous block
+    // whatever its width, so narrow tiles keep many-worker arenas on the LDS-slab kernel
     for (int W = 1024; W >= 64; W >>= 1)
         if ((int64_t)N * W * 4 <= 8 * 1024 && combo::slab_strip_cols(N, R, W) == W) return W;
-    return combo::slab_strip_cols(N, R, 64) == 64 ? 64 : COMBO_ERANGE;
+    for (int W = 64; W >= 8; W >>= 1)
+        if ((int64_t)N * W * 4 <= 32 * 1024 && combo::slab_strip_cols(N, R, W) == W) return W;
+    return combo::slab_strip_cols(N, R, 8) == 8 ? 8 : COMBO_ERANGE;
 }
 
 int combo_pack_tiled(float* d_tiled, const float* d_rows, int64_t ld, int32_t N, int64_t P,

@@ -43,7 +43,7 @@ struct DivArgs {
     int64_t ld;
     int64_t P;
     int32_t N;
-    int32_t W;            // strip width (power of two, 64..512)
+    int32_t W;            // strip width (power of two, 16..512)
     uint32_t nstrips;
     int32_t vec;          // 16-byte aligned with ld % 4 == 0: 128-bit loads allowed
     int32_t tile_shift;   // 0: row-major [N][ld]; else log2(Wt) of a tiled arena [T][N][Wt], W % Wt == 0
@@ -377,17 +377,20 @@ int divergence_threads(int32_t N, int W) {
 }
 
 // strip width: the widest one whose N rows fill at most eight 128-bit words per thread of
-// a 256-thread workgroup (0: N too large)
+// a 256-thread workgroup; for many workers narrower strips (down to 16 columns) with 512
+// threads (0: more than 512 workers)
 int divergence_strip_cols(int32_t N) {
     if (N > kDivThreadsMax) return 0;                // one fold thread per worker
     for (int W = 512; W >= 64; W >>= 1)
         if ((int64_t)N * (W / 4) <= kDivSlots * 256) return W;
-    return (int64_t)N * 16 <= (int64_t)kDivThreadsMax * kDivSlots ? 64 : 0;
+    for (int W = 64; W >= 16; W >>= 1)
+        if ((int64_t)N * (W / 4) <= (int64_t)kDivThreadsMax * kDivSlots) return W;
+    return 0;
 }
 
 // can a strip of W columns (e.g. the tile width of a tiled arena) be handled at all
 bool divergence_width_ok(int32_t N, int W) {
-    return N <= kDivThreadsMax && W >= 64 && W <= 512 && (W & (W - 1)) == 0 &&
+    return N <= kDivThreadsMax && W >= 16 && W <= 512 && (W & (W - 1)) == 0 &&
            (int64_t)N * (W / 4) <= (int64_t)divergence_threads(N, W) * kDivSlots;
 }
 

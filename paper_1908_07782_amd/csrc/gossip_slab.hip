@@ -44,12 +44,13 @@ hipError_t launch_rt(const RoundArgs& a, int W, uint32_t grid, size_t lds, hipSt
 // Strip width: the widest power of two in [64, 1024] columns whose slab is at most
 // 16 KiB (two 128-bit words per thread, four workgroups per compute unit); for many
 // workers 64 columns as long as slab, peer list and weights fit in 64 KiB of LDS.
-// `requested` != 0 forces a width if it fits.
+// `requested` != 0 forces a width if it fits (tiled arenas: their tile width, down to 8
+// columns).
 int slab_strip_cols(int32_t N, int32_t R, int requested) {
     const size_t kLimit = 64 * 1024;
     if (requested) {
         const bool pow2 = (requested & (requested - 1)) == 0;
-        if (pow2 && requested >= 64 && requested <= 1024 &&
+        if (pow2 && requested >= 8 && requested <= 1024 &&
             slab_lds_bytes(N, R, requested) <= kLimit)
             return requested;
     }

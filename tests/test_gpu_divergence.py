@@ -31,7 +31,8 @@ def gpu_divergence(combo, x, P, d=None):
 
 
 @pytest.mark.parametrize("N,P", [(4, 65_536), (12, 30_001), (32, 200_003), (100, 50_003), (1, 5_000),
-                                 (2, 63), (224, 4_097), (256, 1_000), (16, 1_000_000)])
+                                 (2, 63), (224, 4_097), (256, 1_000), (16, 1_000_000), (300, 2_001),
+                                 (512, 1_003)])
 @pytest.mark.parametrize("weighted", [False, True])
 def test_divergence_matches_oracle(combo, ref, N, P, weighted):
     rng = np.random.default_rng(N * 7 + P)
@@ -54,7 +55,9 @@ def test_divergence_matches_oracle(combo, ref, N, P, weighted):
                                     (17, 64 * 4 * 9, 64), (32, 11_689_512 // 16, 64),
                                     # tiles larger than one wavefront's register slots (workgroup kernel), odd row counts
                                     (33, 4_000, 64), (65, 7_000, 64), (128, 9_999, 64), (129, 3_000, 64),
-                                    (40, 5_000, 128), (20, 6_001, 256), (100, 1_000_003 // 4, 64)])
+                                    (40, 5_000, 128), (20, 6_001, 256), (100, 1_000_003 // 4, 64),
+                                    # narrow tiles and up to 512 workers
+                                    (300, 3_001, 16), (512, 2_000, 8), (200, 4_001, 32), (12, 1_000, 8)])
 @pytest.mark.parametrize("weighted", [False, True])
 def test_divergence_tiled_matches_oracle(combo, ref, N, P, Wt, weighted):
     rng = np.random.default_rng(N + P)

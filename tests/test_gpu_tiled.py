@@ -41,7 +41,8 @@ def to_tiled(combo, Xh, Wt):
 
 
 @pytest.mark.parametrize("N,P,Wt", [(4, 1000, 64), (5, 10_007, 128), (32, 40_001, 64), (3, 64, 64),
-                                    (7, 63, 64), (16, 100_000, 1024), (100, 5_003, 64)])
+                                    (7, 63, 64), (16, 100_000, 1024), (100, 5_003, 64),
+                                    (300, 2_001, 16), (5, 1_003, 8), (70, 999, 32), (3, 7, 8)])
 def test_pack_and_unpack_match_numpy(combo, N, P, Wt):
     Xh = np.random.default_rng(P).normal(0, 1, (N, P)).astype(np.float32)
     tiled = to_tiled(combo, Xh, Wt)
@@ -88,6 +89,10 @@ ROUND_CASES = [
     (4, 65_536, 8, 2, 512), (5, 10_007, 7, 3, 64), (8, 40_001, 3, 4, 128), (32, 9_999, 32, 4, 64),
     (7, 4_096, 1, 2, 256), (6, 130, 130, 1, 64), (12, 20_000, 5, 11, 64), (16, 30_011, 4, 9, 128),
     (9, 5_000, 2, 0, 64), (100, 20_003, 7, 3, 64), (2, 8_193, 2, 1, 1024), (32, 70_000, 32, 4, 128),
+    # narrow tiles: many workers on the LDS-slab kernel (more workers than threads in a workgroup,
+    # run-time replica counts), and small cases at every narrow width
+    (300, 5_003, 5, 3, 16), (600, 3_001, 3, 2, 8), (1000, 2_003, 2, 2, 8), (64, 9_999, 4, 4, 32),
+    (12, 1_000, 3, 2, 8), (200, 4_001, 4, 12, 32), (513, 1_500, 3, 1, 16),
 ]
 
 
@@ -113,7 +118,8 @@ def test_tiled_round_matches_oracle(combo, ref, N, P, S, R, Wt, weighted):
 
 
 @pytest.mark.parametrize("tau", [0, 1, 3])
-@pytest.mark.parametrize("N,P,S,R,Wt", [(6, 10_007, 7, 3, 64), (100, 5_003, 7, 3, 64), (16, 30_000, 4, 4, 128)])
+@pytest.mark.parametrize("N,P,S,R,Wt", [(6, 10_007, 7, 3, 64), (100, 5_003, 7, 3, 64), (16, 30_000, 4, 4, 128),
+                                        (300, 2_003, 3, 3, 16), (9, 3_000, 2, 2, 8)])
 def test_tiled_fused_steps_match_oracle(combo, ref, tau, N, P, S, R, Wt):
     rng = np.random.default_rng(tau + N)
     Xh = rng.uniform(-0.1, 0.1, (N, P)).astype(np.float32)
@@ -135,8 +141,8 @@ def test_tiled_fused_steps_match_oracle(combo, ref, tau, N, P, S, R, Wt):
     assert np.array_equal(np_unpack(src.cpu().numpy(), N, P, Wt), Xh)
 
 
-def test_tiled_dynamic_round(combo, ref):
-    N, P, S, R, Wt = 12, 30_011, 6, 3, 128
+@pytest.mark.parametrize("N,P,S,R,Wt", [(12, 30_011, 6, 3, 128), (300, 3_001, 4, 3, 16), (20, 2_000, 3, 4, 8)])
+def test_tiled_dynamic_round(combo, ref, N, P, S, R, Wt):
     st = np.ones(N, np.uint8)
     st[[2, 7]] = 0
     st[[4, 11]] = 2
@@ -164,9 +170,14 @@ def test_tiled_errors(combo):
         combo.segment_gossip_round_tiled(a, a, 64, peers, 4, 1000, 2, 2)
     assert e.value.status == -2
     with pytest.raises(combo.ComboError) as e:
-        combo.tiled_cols(300, 2)
+        combo.tiled_cols(3000, 2)
     assert e.value.status == -3
     assert combo.tiled_cols(32, 4) == 64 and combo.tiled_cols(16, 4) == 128
+    # more workers: the widest of 64, 32, 16, 8 columns whose tile stays within 32 KiB
+    assert combo.tiled_cols(100, 3) == 64 and combo.tiled_cols(200, 3) == 32
+    assert combo.tiled_cols(300, 2) == 16 and combo.tiled_cols(1000, 2) == 8
+    with pytest.raises(combo.ComboError):
+        combo.tiled_elems(4, 1000, 4)
 
 
 @pytest.mark.parametrize("name", ["c2_resnet18", "c3_resnet50", "c4_prime_fused", "c5_bertlarge"])
