@@ -39,6 +39,8 @@ def test_arena_simulation_matches_oracle(combo, ref, layout, selection):
             arena.step(grads=g, lr=0.05)
             X = ref.local_sgd_steps_then_gossip(X.copy(), Gh, 0.05, maker(N, S, R, 11, t), P, S, R, d=d)
         rho.append(arena.divergence().cpu().numpy())
+        # the table of the step just taken stays readable until the next step
+        assert np.array_equal(arena.peers.cpu().numpy()[:N * S * R], maker(N, S, R, 11, t).reshape(-1))
     got = arena.export().cpu().numpy()
     assert np.array_equal(got.view(np.uint32), X.view(np.uint32))
     assert arena.round == T
@@ -61,3 +63,31 @@ def test_arena_dynamic_workers(combo, ref):
         T = ref.make_peer_table_dynamic(st, N, S, R, 4, 0)
         want = ref.gossip_round_dynamic(Xh, T, st, P, S, R)
         assert np.array_equal(arena.export().cpu().numpy().view(np.uint32), want.view(np.uint32))
+
+
+def test_arena_many_short_rounds_with_interleaved_readers_and_dynamic_steps(combo, ref):
+    """Many short rounds without host synchronisation, a serve-load histogram after every
+    step, dynamic steps in the middle."""
+    N, P, S, R, T = 16, 8_195, 4, 3, 24
+    Xh = np.random.default_rng(9).normal(0, 0.05, (N, P)).astype(np.float32)
+    st = np.ones(N, np.uint8)
+    st[[1, 5]] = 0
+    std = torch.from_numpy(st).cuda()
+    arena = combo.GossipArena(N, P, S, R, layout="tiled", seed=3)
+    arena.load(torch.from_numpy(Xh).cuda())
+    degs = []
+    for t in range(T):
+        arena.step(status=std if t in (7, 8, 15) else None)
+        degs.append(arena.serve_load())                  # stays on the device: no host sync in the loop
+    torch.cuda.synchronize()
+    X = Xh
+    for t in range(T):
+        if t in (7, 8, 15):
+            tab = ref.make_peer_table_dynamic(st, N, S, R, 3, t)
+            X = ref.gossip_round_dynamic(X, tab, st, P, S, R)
+        else:
+            tab = ref.make_peer_table(N, S, R, 3, t)
+            X = ref.gossip_round(X, tab, P, S, R)
+        flat = np.asarray(tab).reshape(-1)
+        assert np.array_equal(degs[t].cpu().numpy(), np.bincount(flat[flat >= 0], minlength=N)), t
+    assert np.array_equal(arena.export().cpu().numpy().view(np.uint32), X.view(np.uint32))
