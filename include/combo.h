@@ -30,7 +30,8 @@
  *     undefined behaviour.
  *   - Arithmetic is IEEE binary32 with one rounding per operation (no fused
  *     multiply-add), in the fixed order stated at each entry point, so results are
- *     reproducible bit for bit.
+ *     reproducible bit for bit.  A quotient is the correctly rounded one, however the
+ *     kernel obtains it.
  *   - Fast paths need 16-byte aligned d_dst/d_src/d_grad and ld % 4 == 0; any other
  *     alignment or pitch is accepted and handled by a slower scalar kernel.
  *   - Thread safety: calls are independent; tuning (combo_tune) is process-global.
