@@ -25,6 +25,8 @@ CASES = [
     (4, 65_536, 8, 2), (5, 10_007, 7, 3), (8, 40_001, 3, 4), (32, 9_999, 32, 4), (7, 4_096, 1, 2),
     (6, 130, 130, 1), (9, 5_000, 2, 0), (9, 20_000, 5, 8), (100, 20_003, 7, 3), (2, 8_193, 2, 1),
     (32, 70_000, 32, 4), (16, 30_011, 4, 7), (1, 3_000, 3, 0), (200, 3_001, 3, 5),
+    # many workers: narrow tiles (the row-major slab does not fit: tiled only)
+    (300, 4_003, 4, 3), (600, 2_001, 3, 2),
 ]
 
 
@@ -32,6 +34,8 @@ CASES = [
 @pytest.mark.parametrize("layout", ["rows", "tiled"])
 @pytest.mark.parametrize("mode", ["plain", "weighted", "fused2"])
 def test_hashed_round_matches_oracle(combo, ref, N, P, S, R, layout, mode):
+    if layout == "rows" and combo.round_kernel_kind(N, R) != 1:
+        pytest.skip("N rows of 64 columns do not fit in LDS: the one-launch round needs the tiled arena")
     rng = np.random.default_rng(N * 17 + P + R)
     seed, rnd = int(rng.integers(0, 2**63)), int(rng.integers(0, 2**30))
     Xh = rng.normal(0, 0.05, (N, P)).astype(np.float32)
