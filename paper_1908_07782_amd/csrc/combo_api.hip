@@ -321,11 +321,11 @@ int combo_round_hashed(float* d_dst, const float* d_src, const float* d_grads, i
         if (!tile_cols_ok(tile_cols)) return COMBO_EINVAL;
         elems = (uint64_t)tiled_elems(N, P, tile_cols);
         W = tile_cols;
-        if (combo::slab_strip_cols(N, R, W) != W) return COMBO_ERANGE;
+        if (combo::slab_strip_cols(N, R, W, true) != W) return COMBO_ERANGE;
     } else {
         if (ld < P) return COMBO_EINVAL;
         elems = (uint64_t)N * (uint64_t)ld;
-        W = combo::slab_strip_cols(N, R, g_slab_cols.load());
+        W = combo::slab_strip_cols(N, R, g_slab_cols.load(), true);
         if (W == 0 || ld % 4 != 0) return COMBO_ERANGE;
     }
     if (!aligned16(d_dst) || !aligned16(d_src) || !aligned16(d_grads)) return COMBO_ERANGE;

@@ -69,14 +69,14 @@ hipError_t launch_unpack_tiled(float* rows, int64_t ld, const float* tiled, int3
 
 // Slab kernel: one workgroup stages all N rows of a strip of `strip_cols` columns in
 // LDS.  slab_strip_cols() picks the strip width for N workers (0: does not fit in LDS).
-int slab_strip_cols(int32_t N, int32_t R, int requested);
+int slab_strip_cols(int32_t N, int32_t R, int requested, bool hashed = false);
 hipError_t launch_round_slab(const RoundArgs& a, int strip_cols, hipStream_t st);
 // the same kernel drawing its peers in-kernel from a.hash_sr (R <= 8, no table)
 hipError_t launch_round_slab_hashed(const RoundArgs& a, int strip_cols, hipStream_t st);
 // dynamic-worker variants (a.status != nullptr); grid and LDS size as computed by launch_round_slab
 hipError_t launch_round_slab_dynamic(const RoundArgs& a, int strip_cols, uint32_t grid, size_t lds,
                                      hipStream_t st);
-size_t slab_lds_bytes(int32_t N, int32_t R, int strip_cols);
+size_t slab_lds_bytes(int32_t N, int32_t R, int strip_cols, bool hashed);
 int slab_threads(int32_t N, int strip_cols);
 
 // number of workgroups launch_round would use, or 0 if that exceeds the grid limit

@@ -4,10 +4,10 @@
 
 namespace combo {
 
-size_t slab_lds_bytes(int32_t N, int32_t R, int W) {
-    // slab, peer list, dataset sizes, status (or denominators), swap partners of the
-    // in-kernel draw, reciprocals of the denominators
-    return (size_t)N * (size_t)W * 4 + 2 * (size_t)N * (size_t)R * 4 + 3 * (size_t)N * 4;
+size_t slab_lds_bytes(int32_t N, int32_t R, int W, bool hashed) {
+    // slab, peer list, dataset sizes, status (or denominators), reciprocals of the
+    // denominators; the in-kernel draw adds its swap partners
+    return (size_t)N * (size_t)W * 4 + (hashed ? 2 : 1) * (size_t)N * (size_t)R * 4 + 3 * (size_t)N * 4;
 }
 
 // 256 threads for slabs of up to 768 128-bit words (12 KiB), 512 beyond
@@ -46,23 +46,23 @@ hipError_t launch_rt(const RoundArgs& a, int W, uint32_t grid, size_t lds, hipSt
 // workers 64 columns as long as slab, peer list and weights fit in 64 KiB of LDS.
 // `requested` != 0 forces a width if it fits (tiled arenas: their tile width, down to 8
 // columns).
-int slab_strip_cols(int32_t N, int32_t R, int requested) {
+int slab_strip_cols(int32_t N, int32_t R, int requested, bool hashed) {
     const size_t kLimit = 64 * 1024;
     if (requested) {
         const bool pow2 = (requested & (requested - 1)) == 0;
         if (pow2 && requested >= 8 && requested <= 1024 &&
-            slab_lds_bytes(N, R, requested) <= kLimit)
+            slab_lds_bytes(N, R, requested, hashed) <= kLimit)
             return requested;
     }
     for (int W = 1024; W >= 64; W >>= 1)
-        if ((size_t)N * (size_t)W * 4 <= 16 * 1024 && slab_lds_bytes(N, R, W) <= kLimit) return W;
-    return slab_lds_bytes(N, R, 64) <= kLimit ? 64 : 0;
+        if ((size_t)N * (size_t)W * 4 <= 16 * 1024 && slab_lds_bytes(N, R, W, hashed) <= kLimit) return W;
+    return slab_lds_bytes(N, R, 64, hashed) <= kLimit ? 64 : 0;
 }
 
 hipError_t launch_round_slab(const RoundArgs& a, int W, hipStream_t st) {
     const uint64_t strips = ((uint64_t)a.P + (uint64_t)W - 1) / (uint64_t)W;
     if (strips > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    const size_t lds = slab_lds_bytes(a.N, a.R, W);
+    const size_t lds = slab_lds_bytes(a.N, a.R, W, false);
     const uint32_t grid = (uint32_t)strips;
     if (a.status != nullptr) return launch_round_slab_dynamic(a, W, grid, lds, st);
     switch (a.R) {

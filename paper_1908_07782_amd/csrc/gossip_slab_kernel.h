@@ -62,7 +62,7 @@ __global__ __launch_bounds__(kSlabThreads) void gossip_slab_kernel(const RoundAr
     // static weighted rounds keep each row's denominator (the sizes of the worker and its
     // peers added in list order) and its reciprocal; the slab then holds size * value
     float* lds_den = reinterpret_cast<float*>(lds_status);                        // [N] (no status then)
-    float* lds_rcp = reinterpret_cast<float*>(lds_partner + (size_t)N * (size_t)R);   // [N]
+    float* lds_rcp = reinterpret_cast<float*>(lds_partner + (HASHED ? (size_t)N * (size_t)R : 0));   // [N]
     constexpr bool kPrescaled = WEIGHTED && !DYNAMIC;
 
     const int64_t col0 = (int64_t)blockIdx.x * W;

@@ -91,7 +91,7 @@ ROUND_CASES = [
     (9, 5_000, 2, 0, 64), (100, 20_003, 7, 3, 64), (2, 8_193, 2, 1, 1024), (32, 70_000, 32, 4, 128),
     # narrow tiles: many workers on the LDS-slab kernel (more workers than threads in a workgroup,
     # run-time replica counts), and small cases at every narrow width
-    (300, 5_003, 5, 3, 16), (600, 3_001, 3, 2, 8), (1000, 2_003, 2, 2, 8), (64, 9_999, 4, 4, 32),
+    (300, 5_003, 5, 3, 16), (600, 3_001, 3, 2, 8), (1000, 2_003, 2, 5, 8), (64, 9_999, 4, 4, 32),
     (12, 1_000, 3, 2, 8), (200, 4_001, 4, 12, 32), (513, 1_500, 3, 1, 16),
 ]
 
@@ -175,7 +175,9 @@ def test_tiled_errors(combo):
     assert combo.tiled_cols(32, 4) == 64 and combo.tiled_cols(16, 4) == 128
     # more workers: the widest of 64, 32, 16, 8 columns whose tile stays within 32 KiB
     assert combo.tiled_cols(100, 3) == 64 and combo.tiled_cols(200, 3) == 32
-    assert combo.tiled_cols(300, 2) == 16 and combo.tiled_cols(1000, 2) == 8
+    assert combo.tiled_cols(300, 2) == 16 and combo.tiled_cols(1000, 5) == 8
+    with pytest.raises(combo.ComboError):
+        combo.tiled_cols(1000, 6)                    # the peer list no longer fits beside the slab
     with pytest.raises(combo.ComboError):
         combo.tiled_elems(4, 1000, 4)
 
