@@ -203,7 +203,7 @@ int combo_segment_gossip_round_dynamic(float* d_dst, const float* d_src, int64_t
  *   combo_tiled_cols(N, R)          recommended Wt (a power of two in [8, 1024]: 8 KiB tiles
  *                                   for N <= 32, then the widest of 64, 32, 16, 8 columns
  *                                   whose tile stays within 32 KiB), or a negative status if
- *                                   N rows of 8 columns do not fit in LDS (about N > 1000 + 500/(R+1))
+ *                                   N rows of 8 columns do not fit in LDS (N*(44 + 4*R) > 65536)
  *   combo_tiled_elems(N, P, Wt)     floats in one tiled matrix, = T*N*Wt
  *   combo_pack_tiled / combo_unpack_tiled   convert row-major <-> tiled (pure copies)
  *   combo_segment_gossip_round_tiled        the round of combo_segment_gossip_round on
