@@ -235,16 +235,16 @@ def run_rounds_gpu(combo, wl, arena, rounds, grads=None, dsz=None, tables_out=No
     return cur
 
 
-def oracle_rounds_on_window(ref, wl, Xwin, c0, rounds, Gwins=None):
+def oracle_rounds_on_window(ref, wl, Xwin, c0, rounds, Gwins=None, d=None):
     """The same T rounds in the oracle on the column window [c0, c0 + ncols)."""
     X = np.ascontiguousarray(Xwin)
     for rnd in range(rounds):
         ph = ref.make_peer_table(wl.N, wl.S, wl.R, wl.hash_seed, rnd)
         if Gwins is not None:
             X = ref.local_sgd_then_gossip(X, np.ascontiguousarray(Gwins[rnd]), wl.lr, ph, wl.P, wl.S,
-                                          wl.R, col0=c0)
+                                          wl.R, d=d, col0=c0)
         else:
-            X = ref.gossip_round(X, ph, wl.P, wl.S, wl.R, col0=c0)
+            X = ref.gossip_round(X, ph, wl.P, wl.S, wl.R, d=d, col0=c0)
     return X
 
 

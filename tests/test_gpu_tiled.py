@@ -182,11 +182,16 @@ def test_tiled_errors(combo):
         combo.tiled_elems(4, 1000, 4)
 
 
-@pytest.mark.parametrize("name", ["c2_resnet18", "c3_resnet50", "c4_prime_fused", "c5_bertlarge"])
-def test_full_size_workloads_tiled_on_sampled_windows(combo, ref, name):
+@pytest.mark.parametrize("name,weighted", [("c2_resnet18", False), ("c3_resnet50", False),
+                                           ("c4_prime_fused", False), ("c5_bertlarge", False),
+                                           ("c2_resnet18", True), ("c4_prime_fused", True)])
+def test_full_size_workloads_tiled_on_sampled_windows(combo, ref, name, weighted):
     """Full-size tiled arena, all rounds, the layout and launch configuration that the
-    benchmark times; compared on column windows that the oracle recomputes round by round."""
+    benchmark times (and the same with dataset-size weights); compared on column windows
+    that the oracle recomputes round by round."""
     wl = combo.workloads.WORKLOADS[name]
+    d = combo.workloads.dataset_sizes(wl.N, 1, "cuda") if weighted else None
+    dh = None if d is None else d.cpu().numpy()
     Wt = combo.tiled_cols(wl.N, wl.R)
     n = combo.tiled_elems(wl.N, wl.P, Wt)
     T = n // (wl.N * Wt)
@@ -225,13 +230,15 @@ def test_full_size_workloads_tiled_on_sampled_windows(combo, ref, name):
             for w in wins:
                 G[w].append(window(grads, *w))
             combo.local_sgd_steps_then_gossip_tiled(arena[1 - cur], arena[cur], grads, 1, wl.lr, Wt, peers,
-                                                    wl.N, wl.P, wl.S, wl.R)
+                                                    wl.N, wl.P, wl.S, wl.R, dataset_sizes=d)
         else:
-            combo.segment_gossip_round_tiled(arena[1 - cur], arena[cur], Wt, peers, wl.N, wl.P, wl.S, wl.R)
+            combo.segment_gossip_round_tiled(arena[1 - cur], arena[cur], Wt, peers, wl.N, wl.P, wl.S, wl.R,
+                                             dataset_sizes=d)
         cur = 1 - cur
     torch.cuda.synchronize()
     for w in wins:
-        want = tp.oracle_rounds_on_window(ref, wl, X0[w], w[0], wl.rounds, Gwins=G[w] if wl.fused else None)
+        want = tp.oracle_rounds_on_window(ref, wl, X0[w], w[0], wl.rounds, Gwins=G[w] if wl.fused else None,
+                                          d=dh)
         got = window(arena[cur], *w)
         assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), (name, w)
     # nothing unwritten inside the rows; the last tile's padding columns stay NaN
