@@ -1,4 +1,4 @@
-"""Randomised GPU-vs-oracle parity: 60 seeded random shapes (N, P, S, R, pitch, layout,
+"""Randomised GPU-vs-oracle parity: 84 seeded random shapes (N, P, S, R, pitch, layout,
 weights, fused steps, dynamic status), each compared bit for bit with the CPU oracle."""
 import numpy as np
 import pytest
@@ -20,11 +20,15 @@ def np_unpack(flat, N, P, Wt):
     return np.ascontiguousarray(flat.reshape(T, N, Wt).transpose(1, 0, 2).reshape(N, T * Wt)[:, :P])
 
 
-@pytest.mark.parametrize("case", range(60))
+@pytest.mark.parametrize("case", range(84))
 def test_random_case(combo, ref, case):
     rng = np.random.default_rng(1000 + case)
-    N = int(rng.choice([1, 2, 3, 5, 8, 16, 31, 32, 33, 64, 100, 130, 257]))
-    P = int(rng.choice([1, 7, 63, 64, 65, 1000, 4097, 20_011, 65_536, 100_003]))
+    if case < 60:
+        N = int(rng.choice([1, 2, 3, 5, 8, 16, 31, 32, 33, 64, 100, 130, 257]))
+        P = int(rng.choice([1, 7, 63, 64, 65, 1000, 4097, 20_011, 65_536, 100_003]))
+    else:                                           # many workers: narrow tiles, row-tile fallback
+        N = int(rng.choice([40, 129, 257, 400, 513, 700, 1000]))
+        P = int(rng.choice([9, 500, 4097, 20_011]))
     S = int(rng.integers(1, min(P, 40) + 1))
     R = int(rng.integers(0, min(N - 1, 12) + 1))
     mode = rng.choice(["plain", "weighted", "fused", "dynamic"])
