@@ -290,7 +290,8 @@ int combo_aggregation_divergence_tiled(double* d_dist2, const float* d_x, int32_
  *   COMBO_TUNE_SLAB_COLS   strip width of the slab kernel: 0 = automatic, or a power of
  *                          two in [64, 1024] (ignored if that slab does not fit in LDS)
  *   COMBO_TUNE_TILE_COLS   row-tile kernel: columns of one worker handled by one
- *                          workgroup: 1024, 2048 or 4096
+ *                          workgroup: 0 = automatic (2048, or 1024 for more than 384
+ *                          workers), or 1024, 2048, 4096
  *   COMBO_TUNE_XCD_SWIZZLE row-tile kernel: 1: consecutive workgroups on one XCD are the
  *                          N workers of one column tile (peer rows are re-read from that
  *                          XCD's L2); 0: plain worker-major order

@@ -9,7 +9,7 @@
 
 namespace {
 
-std::atomic<int> g_tile_cols{2048};
+std::atomic<int> g_tile_cols{0};              // 0: by the number of workers
 std::atomic<int> g_swizzle{1};
 std::atomic<int> g_fused_mode{0};
 std::atomic<int> g_kernel{0};
@@ -39,6 +39,22 @@ int check_round_args(const float* dst, const float* src, int64_t ld, const int32
     return COMBO_OK;
 }
 
+// Columns of one worker per workgroup of the row-tile kernel.  The N workers of a column
+// tile run back to back on one XCD and re-read each other's rows from its 4 MiB L2, so
+// the tile has to shrink as N grows (measured: N = 1000, 4.50 TB/s at 1024 columns against
+// 3.96 at 2048 and 3.24 at 4096; up to N = 300 2048 is at least as good, from N = 500
+// on 1024 is better).  A forced value
+// or, if the grid would be too large, the next wider tile wins.
+int row_tile_cols(int32_t N, int64_t P) {
+    const int forced = g_tile_cols.load();
+    if (forced != 0) return forced;
+    const bool swizzle = g_swizzle.load() != 0;
+    const int first = N > 384 ? 1024 : 2048;
+    for (int t = first; t <= 4096; t <<= 1)
+        if (combo::round_grid_size(N, P, t, swizzle) != 0) return t;
+    return 4096;
+}
+
 // Enqueue one aggregation round.  grad != nullptr: the local step is fused into the
 // round (only possible with the slab kernel); the caller has checked that with
 // fused_in_round().
@@ -46,7 +62,7 @@ int enqueue_round(float* dst, const float* src, const float* grad, float lr, int
                   const int32_t* peers, const float* dsz, int32_t N, int64_t P, int32_t S,
                   int32_t R, Plan plan, hipStream_t st, const uint8_t* status = nullptr,
                   int32_t tau = 1, int arena_tile = 0, bool hashed = false, uint64_t hash_sr = 0) {
-    const int tile_cols = g_tile_cols.load();
+    const int tile_cols = row_tile_cols(N, P);
     const bool swizzle = g_swizzle.load() != 0;
     combo::RoundArgs a;
     a.dst = dst;
@@ -192,7 +208,7 @@ int combo_local_sgd_steps_then_gossip(float* d_dst, float* d_src, const float* d
                              plan, st, nullptr, tau);
     // separate passes: step every row in place tau times, then the plain round
     if ((plan.kind == kPlanTile &&
-         combo::round_grid_size(N, P, g_tile_cols.load(), g_swizzle.load() != 0) == 0) ||
+         combo::round_grid_size(N, P, row_tile_cols(N, P), g_swizzle.load() != 0) == 0) ||
         combo::round_grid_size(N, P, 4096, false) == 0)
         return COMBO_ERANGE;
     const bool vec = aligned16(d_src) && aligned16(d_grads) && (ld % 4 == 0);
@@ -397,7 +413,7 @@ int combo_round_kernel_kind(int32_t N, int32_t R) {
 int combo_tune(int key, int value) {
     switch (key) {
         case COMBO_TUNE_TILE_COLS:
-            if (value != 1024 && value != 2048 && value != 4096) return COMBO_EINVAL;
+            if (value != 0 && value != 1024 && value != 2048 && value != 4096) return COMBO_EINVAL;
             g_tile_cols.store(value);
             return COMBO_OK;
         case COMBO_TUNE_XCD_SWIZZLE:

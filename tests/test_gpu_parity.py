@@ -45,7 +45,7 @@ def _default_tuning(combo):
     combo.tune(combo.TUNE_KERNEL, 0)
     combo.tune(combo.TUNE_SLAB_COLS, 0)
     combo.tune(combo.TUNE_FUSED_MODE, 0)
-    combo.tune(combo.TUNE_TILE_COLS, 2048)
+    combo.tune(combo.TUNE_TILE_COLS, 0)
     combo.tune(combo.TUNE_XCD_SWIZZLE, 1)
 
 
