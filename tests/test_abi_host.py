@@ -163,7 +163,24 @@ def test_fused_argument_errors(L):
     assert call(R=9) == EINVAL
 
 
+def test_tiled_layout_sizes_and_recommended_widths(L):
+    """Pure host arithmetic: which tile width the library recommends and how many floats a
+    tiled matrix has."""
+    cols, elems = L.combo_tiled_cols, L.combo_tiled_elems
+    assert cols(0, 1) == EINVAL and cols(4, -1) == EINVAL
+    # 8 KiB tiles while a row chunk keeps at least 64 columns
+    assert [cols(n, 4) for n in (4, 8, 16, 32)] == [512, 256, 128, 64] and cols(2, 1) == 1024
+    # then the widest of 64, 32, 16, 8 columns whose tile stays within 32 KiB
+    assert [cols(n, 3) for n in (33, 100, 128, 129, 256, 257, 512, 513, 1000)] == \
+        [64, 64, 64, 32, 32, 16, 16, 8, 8]
+    assert cols(1000, 5) == 8 and cols(1000, 6) == ERANGE and cols(3000, 2) == ERANGE
+    assert elems(4, 1000, 64) == 16 * 4 * 64 and elems(7, 63, 8) == 8 * 7 * 8
+    assert elems(4, 1000, 4) == EINVAL and elems(4, 1000, 100) == EINVAL and elems(4, 1000, 2048) == EINVAL
+    assert elems(0, 1000, 64) == EINVAL and elems(4, 0, 64) == EINVAL
+
+
 def test_tuning_knobs(L):
+    assert L.combo_get_tune(0) == 0                  # row-tile width: automatic
     assert L.combo_tune(0, 1000) == EINVAL
     assert L.combo_tune(99, 1) == EINVAL
     old = L.combo_get_tune(0)
