@@ -268,7 +268,7 @@ int combo_round_hashed(float* d_dst, const float* d_src, const float* d_grads, i
  *                before and after the call
  * combo_aggregation_divergence_tiled reads a tiled matrix [T][N][tile_cols] instead.
  * Errors: COMBO_EINVAL for bad sizes, NULL pointers, a workspace that is too small or
- * misaligned; COMBO_ERANGE for N > 512, or when N rows of a tile exceed the kernel's
+ * misaligned; COMBO_ERANGE for N > 1024, or when N rows of a tile exceed the kernel's
  * register slots (N * tile_cols > 16384).
  * combo_aggregation_divergence_workspace returns the byte count (4096*N*8), or a negative
  * status.

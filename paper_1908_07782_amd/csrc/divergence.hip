@@ -32,6 +32,7 @@ namespace combo {
 namespace {
 
 constexpr int kDivThreadsMax = 512;
+constexpr int kDivFold = 2;    // worker rows folded per thread at the end: N <= 2 * threads
 constexpr int kDivSlots = 8;   // 128-bit words per thread and strip; filling all eight
                                // (measured: 2 words 2.8, 4 words 4.7, 8 words 6.0 TB/s) keeps
                                // enough loads in flight for the persistent workgroups
@@ -178,8 +179,10 @@ __global__ __launch_bounds__(kDivThreads) void divergence_partial_kernel(const D
     }
 
     // fold: slot k of thread t belongs to row k*groups + t/W4; add a row's threads in
-    // thread order, slot by slot
-    double row_sum = 0.0;
+    // thread order, slot by slot.  Thread t folds rows t and t + kDivThreads.
+    double row_sum[kDivFold];
+#pragma unroll
+    for (int m = 0; m < kDivFold; ++m) row_sum[m] = 0.0;
 #pragma unroll
     for (int k = 0; k < kDivSlots; ++k) {
         if (k * kDivThreads < total4) {               // uniform
@@ -187,12 +190,20 @@ __global__ __launch_bounds__(kDivThreads) void divergence_partial_kernel(const D
             fold[t] = acc[k];
             __syncthreads();
             // row r is served in this pass by threads [ (r - k*groups)*W4, +W4 ) if in range
-            const int g = t - k * groups;             // candidate: thread t folds row t
-            if (t < N && g >= 0 && g < groups)
-                for (int i = 0; i < W4; ++i) row_sum += fold[g * W4 + i];
+#pragma unroll
+            for (int m = 0; m < kDivFold; ++m) {
+                const int r = t + m * kDivThreads;
+                const int g = r - k * groups;
+                if (r < N && g >= 0 && g < groups)
+                    for (int i = 0; i < W4; ++i) row_sum[m] += fold[g * W4 + i];
+            }
         }
     }
-    if (t < N) a.partial[(size_t)t * (size_t)gridDim.x + (size_t)blockIdx.x] = row_sum;   // [N][grid]
+#pragma unroll
+    for (int m = 0; m < kDivFold; ++m) {
+        const int r = t + m * kDivThreads;
+        if (r < N) a.partial[(size_t)r * (size_t)gridDim.x + (size_t)blockIdx.x] = row_sum[m];   // [N][grid]
+    }
 }
 
 // dist2[r] = sum over workgroups of partial[r][b]: one workgroup per worker row, each
@@ -378,9 +389,9 @@ int divergence_threads(int32_t N, int W) {
 
 // strip width: the widest one whose N rows fill at most eight 128-bit words per thread of
 // a 256-thread workgroup; for many workers narrower strips (down to 16 columns) with 512
-// threads (0: more than 512 workers)
+// threads (0: more than 1024 workers)
 int divergence_strip_cols(int32_t N) {
-    if (N > kDivThreadsMax) return 0;                // one fold thread per worker
+    if (N > kDivFold * kDivThreadsMax) return 0;     // fold capacity of the largest workgroup
     for (int W = 512; W >= 64; W >>= 1)
         if ((int64_t)N * (W / 4) <= kDivSlots * 256) return W;
     for (int W = 64; W >= 16; W >>= 1)
@@ -390,7 +401,7 @@ int divergence_strip_cols(int32_t N) {
 
 // can a strip of W columns (e.g. the tile width of a tiled arena) be handled at all
 bool divergence_width_ok(int32_t N, int W) {
-    return N <= kDivThreadsMax && W >= 16 && W <= 512 && (W & (W - 1)) == 0 &&
+    return N <= kDivFold * divergence_threads(N, W) && W >= 16 && W <= 512 && (W & (W - 1)) == 0 &&
            (int64_t)N * (W / 4) <= (int64_t)divergence_threads(N, W) * kDivSlots;
 }
 

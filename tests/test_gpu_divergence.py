@@ -32,7 +32,7 @@ def gpu_divergence(combo, x, P, d=None):
 
 @pytest.mark.parametrize("N,P", [(4, 65_536), (12, 30_001), (32, 200_003), (100, 50_003), (1, 5_000),
                                  (2, 63), (224, 4_097), (256, 1_000), (16, 1_000_000), (300, 2_001),
-                                 (512, 1_003)])
+                                 (512, 1_003), (513, 1_003), (1000, 2_001), (1024, 700)])
 @pytest.mark.parametrize("weighted", [False, True])
 def test_divergence_matches_oracle(combo, ref, N, P, weighted):
     rng = np.random.default_rng(N * 7 + P)
@@ -57,7 +57,8 @@ def test_divergence_matches_oracle(combo, ref, N, P, weighted):
                                     (33, 4_000, 64), (65, 7_000, 64), (128, 9_999, 64), (129, 3_000, 64),
                                     (40, 5_000, 128), (20, 6_001, 256), (100, 1_000_003 // 4, 64),
                                     # narrow tiles and up to 512 workers
-                                    (300, 3_001, 16), (512, 2_000, 8), (200, 4_001, 32), (12, 1_000, 8)])
+                                    (300, 3_001, 16), (512, 2_000, 8), (200, 4_001, 32), (12, 1_000, 8),
+                                    (1000, 2_003, 8), (700, 1_500, 16)])
 @pytest.mark.parametrize("weighted", [False, True])
 def test_divergence_tiled_matches_oracle(combo, ref, N, P, Wt, weighted):
     rng = np.random.default_rng(N + P)
@@ -117,7 +118,7 @@ def test_divergence_on_the_benchmark_workload(combo, ref):
 def test_divergence_errors(combo):
     x = torch.zeros((300, 1024), dtype=torch.float32, device="cuda")
     with pytest.raises(combo.ComboError) as e:
-        combo.aggregation_divergence_workspace(600, 1000)
+        combo.aggregation_divergence_workspace(1100, 1000)
     assert e.value.status == -3
     with pytest.raises(combo.ComboError) as e:          # 100 rows of a 1024-column tile: too many slots
         combo.aggregation_divergence_tiled(torch.zeros(100, dtype=torch.float64, device="cuda"),
