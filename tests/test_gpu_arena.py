@@ -91,3 +91,34 @@ def test_arena_many_short_rounds_with_interleaved_readers_and_dynamic_steps(comb
         flat = np.asarray(tab).reshape(-1)
         assert np.array_equal(degs[t].cpu().numpy(), np.bincount(flat[flat >= 0], minlength=N)), t
     assert np.array_equal(arena.export().cpu().numpy().view(np.uint32), X.view(np.uint32))
+
+
+@pytest.mark.parametrize("selection", ["segment", "pooled"])
+def test_arena_with_many_workers(combo, ref, selection):
+    """600 workers: 8- or 16-column tiles keep the arena on the LDS-slab kernel; table,
+    rounds, fused steps and the divergence monitor against the oracle."""
+    N, P, S, R, T = 600, 3_001, 3, 2, 3
+    rng = np.random.default_rng(21)
+    Xh = rng.normal(0, 0.05, (N, P)).astype(np.float32)
+    d = rng.integers(100, 2000, N).astype(np.float32)
+    arena = combo.GossipArena(N, P, S, R, layout="tiled", seed=5, dataset_sizes=d, selection=selection)
+    assert arena.tile_cols in (8, 16)
+    arena.load(torch.from_numpy(Xh).cuda())
+    maker = ref.make_peer_table_pooled if selection == "pooled" else ref.make_peer_table
+    X = Xh
+    for t in range(T):
+        if t == 1:
+            Gh = rng.normal(0, 1e-2, (1, N, P)).astype(np.float32)
+            g = arena.like_front(1)
+            arena.pack_like_front(g[0], torch.from_numpy(Gh[0]).cuda())
+            arena.step(grads=g, lr=0.05)
+            X = ref.local_sgd_steps_then_gossip(X.copy(), Gh, 0.05, maker(N, S, R, 5, t), P, S, R, d=d)
+        else:
+            arena.step()
+            X = ref.gossip_round(X, maker(N, S, R, 5, t), P, S, R, d=d)
+    assert np.array_equal(arena.export().cpu().numpy().view(np.uint32), X.view(np.uint32))
+    want_rho = ref.aggregation_divergence(X, d=d)
+    got_rho = arena.divergence().cpu().numpy()
+    assert np.all(np.abs(got_rho - want_rho) <= 2e-12 * want_rho)
+    deg = arena.serve_load().cpu().numpy()
+    assert np.array_equal(deg, ref.peer_in_degree(maker(N, S, R, 5, T - 1), N, S, R))
