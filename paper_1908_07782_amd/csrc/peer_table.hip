@@ -87,7 +87,11 @@ __global__ __launch_bounds__(64) void peer_table_pooled_kernel(int32_t* __restri
         }
         __syncthreads();
         if (lane == 0) {
-            for (int32_t i = 0; i + 1 < M; ++i) {           // full Fisher-Yates
+            // Fisher-Yates fixes position i at step i, and this permutation hands out at most
+            // `left` elements after skipping at most R-1: later steps cannot change what is used
+            const int64_t left = requests - served;
+            const int32_t steps = left + R < (int64_t)(M - 1) ? (int32_t)(left + R) : M - 1;
+            for (int32_t i = 0; i < steps; ++i) {
                 const int32_t r = partner[i];
                 const uint16_t t = queue[i];
                 queue[i] = queue[r];
@@ -160,7 +164,12 @@ __global__ __launch_bounds__(64) void peer_table_pooled_wave_kernel(int32_t* __r
             partner = lane + (int32_t)(((word >> 32) * (uint64_t)(uint32_t)(M - lane)) >> 32);
         }
         int32_t where = lane;                     // position of the element that starts in this lane
-        for (int32_t i = 0; i + 1 < M; ++i) {     // full Fisher-Yates: step i swaps positions i and r
+        // Fisher-Yates: step i swaps positions i and r >= i, so position i is final after step
+        // i; this permutation hands out at most `left` elements after skipping at most R-1,
+        // and later steps cannot change what is used
+        const int64_t left_now = requests - served;
+        const int32_t steps = left_now + R < (int64_t)(M - 1) ? (int32_t)(left_now + R) : M - 1;
+        for (int32_t i = 0; i < steps; ++i) {
             const int32_t r = __builtin_amdgcn_readlane(partner, i);
             where = where == i ? r : (where == r ? i : where);
         }
