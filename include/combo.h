@@ -282,6 +282,28 @@ int combo_aggregation_divergence_tiled(double* d_dist2, const float* d_x, int32_
                                        void* d_workspace, int64_t workspace_bytes, void* stream);
 
 /*
+ * The divergence monitor for callers that cannot allocate device memory or pass a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same kernels, arithmetic and results as combo_aggregation_divergence
+ * (tile_cols == 0: row-major d_x with pitch ld) and combo_aggregation_divergence_tiled
+ * (tile_cols != 0: tiled d_x, ld ignored), bit for bit; the per-workgroup partial sums go
+ * to an array the library holds itself in device memory (4 MiB, one copy on every GPU the
+ * library runs on, until the process ends).  Its address is looked up on the first call on
+ * a device; no call allocates, frees or copies memory.
+ *   - At most COMBO_DIVERGENCE_NOALLOC_MAX_WORKERS workers; more return COMBO_ERANGE (use the
+ *     workspace forms then).
+ *   - All calls on one GPU share the one array: calls that may run at the same time on that
+ *     GPU (different streams, different threads) race on it and must be serialised by the
+ *     caller.  Calls on one stream are ordered and safe.  Nothing in the array needs to be
+ *     cleared between calls: every entry that is read has been written by the same call.
+ * Errors: as the workspace forms, plus COMBO_EHIP when the array's address cannot be obtained.
+ */
+#define COMBO_DIVERGENCE_NOALLOC_MAX_WORKERS 128
+int combo_aggregation_divergence_noalloc(double* d_dist2, const float* d_x, int64_t ld,
+                                         int32_t tile_cols, const float* d_dataset_sizes, int32_t N,
+                                         int64_t P, void* stream);
+
+/*
  * Performance knobs (process-global, host side only; results never depend on them).
  *   COMBO_TUNE_KERNEL      0: automatic (LDS-slab kernel when the buffers are 16-byte
  *                          aligned, ld % 4 == 0 and N rows of a 64-column strip fit in

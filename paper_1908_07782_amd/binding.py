@@ -13,7 +13,7 @@ TUNE_FUSED_MODE = 2
 TUNE_KERNEL = 3
 TUNE_SLAB_COLS = 4
 
-EXPORTS = ("combo_round_hashed", "combo_round_kernel_kind", "combo_aggregation_divergence_tiled", "combo_tiled_cols", "combo_tiled_elems", "combo_pack_tiled", "combo_unpack_tiled",
+EXPORTS = ("combo_aggregation_divergence_noalloc", "combo_round_hashed", "combo_round_kernel_kind", "combo_aggregation_divergence_tiled", "combo_tiled_cols", "combo_tiled_elems", "combo_pack_tiled", "combo_unpack_tiled",
            "combo_segment_gossip_round_tiled", "combo_local_sgd_steps_then_gossip_tiled",
            "combo_local_sgd_steps_then_gossip", "combo_aggregation_divergence", "combo_aggregation_divergence_workspace",
            "combo_make_peer_table_dynamic", "combo_segment_gossip_round_dynamic",
@@ -81,6 +81,8 @@ def lib():
         L.combo_local_sgd_steps_then_gossip_tiled.restype = ctypes.c_int
         L.combo_aggregation_divergence_tiled.argtypes = [vp, vp, i32, vp, i32, i64, vp, i64, vp]
         L.combo_aggregation_divergence_tiled.restype = ctypes.c_int
+        L.combo_aggregation_divergence_noalloc.argtypes = [vp, vp, i64, i32, vp, i32, i64, vp]
+        L.combo_aggregation_divergence_noalloc.restype = ctypes.c_int
         L.combo_round_hashed.argtypes = [vp, vp, vp, i32, f32, i64, i32, vp, i32, i64, i32, i32, u64, u64, vp]
         L.combo_round_hashed.restype = ctypes.c_int
         L.combo_round_kernel_kind.argtypes = [i32, i32]
@@ -370,6 +372,28 @@ def aggregation_divergence_tiled(dist2, x, tile_cols, N, P, workspace, dataset_s
         _stream_ptr(stream))
     if rc:
         raise ComboError(rc, "combo_aggregation_divergence_tiled")
+    return dist2
+
+
+def aggregation_divergence_noalloc(dist2, x, N, P, tile_cols=0, dataset_sizes=None, stream=None):
+    """combo_aggregation_divergence_noalloc: the divergence monitor without a workspace
+    argument.  tile_cols == 0: x is an (N, ld)-strided matrix; else a flat tiled buffer."""
+    if dist2.numel() < N or not dist2.is_contiguous():
+        raise ValueError("dist2: need a contiguous float64 device tensor with N entries")
+    if dataset_sizes is not None and (dataset_sizes.numel() < N or not dataset_sizes.is_contiguous()):
+        raise ValueError("dataset_sizes: need a contiguous float32 device tensor with N entries")
+    if tile_cols:
+        ld, px = 0, _flat(x, tiled_elems(N, P, tile_cols), "x")
+    else:
+        if x.shape[0] != N:
+            raise ValueError("x: need N rows")
+        ld, px = _matrix(x, "x"), _dev_ptr(x, torch.float32, "x")
+    rc = lib().combo_aggregation_divergence_noalloc(
+        _dev_ptr(dist2, torch.float64, "dist2"), px, ld, tile_cols,
+        _dev_ptr(dataset_sizes, torch.float32, "dataset_sizes", optional=True), N, P,
+        _stream_ptr(stream))
+    if rc:
+        raise ComboError(rc, "combo_aggregation_divergence_noalloc")
     return dist2
 
 

@@ -360,48 +360,89 @@ int combo_round_hashed(float* d_dst, const float* d_src, const float* d_grads, i
 int64_t combo_aggregation_divergence_workspace(int32_t N, int64_t P) {
     if (N < 1 || P < 1) return COMBO_EINVAL;
     if (combo::divergence_strip_cols(N) == 0) return COMBO_ERANGE;
-    return (int64_t)4096 * (int64_t)N * (int64_t)sizeof(double);   // one partial per workgroup and row
+    // one partial per workgroup and row
+    return (int64_t)combo::kDivPartialsPerRow * (int64_t)N * (int64_t)sizeof(double);
 }
 
-int combo_aggregation_divergence(double* d_dist2, const float* d_x, int64_t ld,
-                                 const float* d_dataset_sizes, int32_t N, int64_t P,
-                                 void* d_workspace, int64_t workspace_bytes, void* stream) {
-    if (N < 1 || P < 1 || ld < P || d_dist2 == nullptr || d_x == nullptr) return COMBO_EINVAL;
+namespace {
+
+// argument checks shared by the divergence entry points; tile_cols == 0: row-major.
+// *strip receives the strip width of the workgroup kernel.
+int check_divergence_args(const double* d_dist2, const float* d_x, int64_t ld, int32_t tile_cols,
+                          int32_t N, int64_t P, int* strip) {
+    if (N < 1 || P < 1 || d_dist2 == nullptr || d_x == nullptr) return COMBO_EINVAL;
+    int W = combo::divergence_strip_cols(N);
+    if (W == 0) return COMBO_ERANGE;
+    if (tile_cols != 0) {
+        if (!tile_cols_ok(tile_cols) || !aligned16(d_x)) return COMBO_EINVAL;
+        if (W < tile_cols) W = tile_cols;             // a strip spans W / tile_cols whole tiles
+        if (!combo::divergence_width_ok(N, W)) return COMBO_ERANGE;
+    } else if (ld < P) {
+        return COMBO_EINVAL;
+    }
+    *strip = W;
+    return COMBO_OK;
+}
+
+// the divergence kernels behind every divergence entry point (arguments already checked)
+int enqueue_divergence(double* d_dist2, const float* d_x, int64_t ld, int32_t tile_cols,
+                       const float* d_dataset_sizes, int32_t N, int64_t P, int W, void* d_workspace,
+                       int64_t workspace_bytes, hipStream_t st) {
     const int64_t need = combo_aggregation_divergence_workspace(N, P);
     if (need < 0) return (int)need;
     if (d_workspace == nullptr || workspace_bytes < need || ((uintptr_t)d_workspace & 7u) != 0)
         return COMBO_EINVAL;
-    const int W = combo::divergence_strip_cols(N);
-    const bool vec = aligned16(d_x) && (ld % 4 == 0);
-    const hipError_t e = combo::launch_divergence(d_dist2, (double*)d_workspace, d_x, ld,
-                                                  d_dataset_sizes, N, P, W, vec, 0,
-                                                  (hipStream_t)stream);
+    hipError_t e;
+    if (tile_cols == 0)
+        e = combo::launch_divergence(d_dist2, (double*)d_workspace, d_x, ld, d_dataset_sizes, N, P, W,
+                                     aligned16(d_x) && (ld % 4 == 0), 0, st);
+    else if (combo::divergence_tile_fits(N, tile_cols))   // small tiles: one wavefront per tile
+        e = combo::launch_divergence_tiles(d_dist2, (double*)d_workspace, d_x, d_dataset_sizes, N, P,
+                                           tile_cols, st);
+    else
+        e = combo::launch_divergence(d_dist2, (double*)d_workspace, d_x, tile_cols, d_dataset_sizes,
+                                     N, P, W, true, tile_cols, st);
     return e == hipSuccess ? COMBO_OK : COMBO_EHIP;
+}
+
+}  // namespace
+
+int combo_aggregation_divergence(double* d_dist2, const float* d_x, int64_t ld,
+                                 const float* d_dataset_sizes, int32_t N, int64_t P,
+                                 void* d_workspace, int64_t workspace_bytes, void* stream) {
+    int W = 0;
+    const int rc = check_divergence_args(d_dist2, d_x, ld, 0, N, P, &W);
+    if (rc != COMBO_OK) return rc;
+    return enqueue_divergence(d_dist2, d_x, ld, 0, d_dataset_sizes, N, P, W, d_workspace,
+                              workspace_bytes, (hipStream_t)stream);
 }
 
 int combo_aggregation_divergence_tiled(double* d_dist2, const float* d_x, int32_t tile_cols,
                                        const float* d_dataset_sizes, int32_t N, int64_t P,
                                        void* d_workspace, int64_t workspace_bytes, void* stream) {
-    if (N < 1 || P < 1 || !tile_cols_ok(tile_cols) || d_dist2 == nullptr || d_x == nullptr ||
-        !aligned16(d_x))
-        return COMBO_EINVAL;
-    int W = combo::divergence_strip_cols(N);         // a strip spans W / tile_cols whole tiles
-    if (W < tile_cols) W = tile_cols;
-    if (!combo::divergence_width_ok(N, W)) return COMBO_ERANGE;
-    const int64_t need = combo_aggregation_divergence_workspace(N, P);
-    if (need < 0) return (int)need;
-    if (d_workspace == nullptr || workspace_bytes < need || ((uintptr_t)d_workspace & 7u) != 0)
-        return COMBO_EINVAL;
-    if (combo::divergence_tile_fits(N, tile_cols)) {  // small tiles: one wavefront per tile
-        const hipError_t e = combo::launch_divergence_tiles(d_dist2, (double*)d_workspace, d_x,
-                                                            d_dataset_sizes, N, P, tile_cols,
-                                                            (hipStream_t)stream);
-        return e == hipSuccess ? COMBO_OK : COMBO_EHIP;
-    }
-    const hipError_t e = combo::launch_divergence(d_dist2, (double*)d_workspace, d_x, tile_cols,
-                                                  d_dataset_sizes, N, P, W, true, tile_cols,
-                                                  (hipStream_t)stream);
-    return e == hipSuccess ? COMBO_OK : COMBO_EHIP;
+    if (tile_cols == 0) return COMBO_EINVAL;
+    int W = 0;
+    const int rc = check_divergence_args(d_dist2, d_x, 0, tile_cols, N, P, &W);
+    if (rc != COMBO_OK) return rc;
+    return enqueue_divergence(d_dist2, d_x, 0, tile_cols, d_dataset_sizes, N, P, W, d_workspace,
+                              workspace_bytes, (hipStream_t)stream);
+}
+
+static_assert(COMBO_DIVERGENCE_NOALLOC_MAX_WORKERS == combo::kDivStaticRows,
+              "the header's limit is the number of rows the held array has room for");
+
+int combo_aggregation_divergence_noalloc(double* d_dist2, const float* d_x, int64_t ld,
+                                         int32_t tile_cols, const float* d_dataset_sizes, int32_t N,
+                                         int64_t P, void* stream) {
+    int W = 0;
+    const int rc = check_divergence_args(d_dist2, d_x, ld, tile_cols, N, P, &W);
+    if (rc != COMBO_OK) return rc;
+    if (N > COMBO_DIVERGENCE_NOALLOC_MAX_WORKERS) return COMBO_ERANGE;   // beyond the held array
+    double* held = nullptr;
+    int64_t held_bytes = 0;
+    if (combo::divergence_static_workspace(&held, &held_bytes) != hipSuccess) return COMBO_EHIP;
+    return enqueue_divergence(d_dist2, d_x, ld, tile_cols, d_dataset_sizes, N, P, W, held, held_bytes,
+                              (hipStream_t)stream);
 }
 
 int combo_round_kernel_kind(int32_t N, int32_t R) {

@@ -49,6 +49,8 @@ hipError_t launch_peer_in_degree(int32_t* deg, const int32_t* peers, int32_t N, 
                                  hipStream_t st);
 
 // Aggregation divergence (divergence.hip)
+constexpr int kDivPartialsPerRow = 4096;   // workspace: at most this many workgroup partials per worker row
+constexpr int kDivStaticRows = 128;        // worker rows the library-held workspace has room for
 int divergence_strip_cols(int32_t N);
 bool divergence_width_ok(int32_t N, int strip_cols);
 hipError_t launch_divergence(double* dist2, double* workspace, const float* x, int64_t ld,
@@ -60,6 +62,9 @@ bool divergence_tile_fits(int32_t N, int tile_cols);
 hipError_t launch_divergence_tiles(double* dist2, double* workspace, const float* x,
                                    const float* dsz, int32_t N, int64_t P, int tile_cols,
                                    hipStream_t st);
+
+// the workspace the library holds itself (a static device array, one per GPU) and its size
+hipError_t divergence_static_workspace(double** workspace, int64_t* bytes);
 
 // layout conversion kernels (layout.hip)
 hipError_t launch_pack_tiled(float* tiled, const float* rows, int64_t ld, int32_t N, int64_t P,

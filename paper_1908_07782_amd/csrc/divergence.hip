@@ -25,11 +25,19 @@
 // a wavefront owns whole tiles, its 64 lanes cover 64/(Wt/4) adjacent rows of the tile per
 // slot, so every load instruction reads one contiguous kilobyte, the column sums are
 // complete after the xor-shuffle tree, and the strip loop needs neither LDS nor barriers.
+#include <mutex>
+
 #include "combo_internal.h"
 #include "round_device.h"
 
 namespace combo {
 namespace {
+
+// Partial sums for callers that cannot bring a workspace (see divergence_static_workspace):
+// one [rows][4096 workgroups] block of binary64 partials, 4 MiB, held by every GPU the
+// library runs on until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; kernels and host calls use the address obtained from it.
+static __device__ __align__(256) double scratch[(size_t)kDivPartialsPerRow * kDivStaticRows];
 
 constexpr int kDivThreadsMax = 512;
 constexpr int kDivFold = 2;    // worker rows folded per thread at the end: N <= 2 * threads
@@ -431,7 +439,7 @@ hipError_t launch_divergence(double* dist2, double* workspace, const float* x, i
             return hipErrorUnknown;
         res = per_cu * cus;
         if (res < 1) res = 256;
-        if (res > 4096) res = 4096;                  // the workspace holds 4096 partials per row
+        if (res > kDivPartialsPerRow) res = kDivPartialsPerRow;   // the workspace's partials per row
     }
     const uint32_t grid = (uint32_t)(strips < (uint64_t)res ? strips : (uint64_t)res);
     DivArgs a;
@@ -463,6 +471,30 @@ hipError_t launch_divergence(double* dist2, double* workspace, const float* x, i
     return hipGetLastError();
 }
 
+// Device address of the library-held workspace on the current device.  Every GPU has its
+// own copy of the array at its own address, so the lookup is done once per device, with
+// that device current, and remembered.
+hipError_t divergence_static_workspace(double** workspace, int64_t* bytes) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex guard;
+    static double* known[kMaxDevices] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(guard);
+    if (known[dev] == nullptr) {
+        double* p = nullptr;
+        e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (p == nullptr) return hipErrorInvalidSymbol;
+        known[dev] = p;
+    }
+    *workspace = known[dev];
+    *bytes = (int64_t)sizeof(double) * kDivPartialsPerRow * kDivStaticRows;
+    return hipSuccess;
+}
+
 bool divergence_tile_fits(int32_t N, int tile_cols) {
     return (tile_cols == 64 || tile_cols == 128 || tile_cols == 256) &&
            (int64_t)N * (tile_cols / 4) <= 64 * kDivSlots;
@@ -486,7 +518,7 @@ hipError_t launch_divergence_tiles(double* dist2, double* workspace, const float
             return hipErrorUnknown;
         res = per_cu * cus;
         if (res < 1) res = 256;
-        if (res > 4096) res = 4096;                  // the workspace holds 4096 partials per row
+        if (res > kDivPartialsPerRow) res = kDivPartialsPerRow;   // the workspace's partials per row
     }
     TileDivArgs a;
     a.partial = workspace;

@@ -105,6 +105,21 @@ def test_divergence_argument_errors(L):
     assert f(FAKE_A, FAKE_B, 1024, None, 4, 1000, ctypes.c_void_p(0x30000004), 10**6, None) == EINVAL
 
 
+def test_divergence_noalloc_argument_errors(L):
+    f = L.combo_aggregation_divergence_noalloc
+    f.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p,
+                  ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p]
+    assert f(None, FAKE_B, 1024, 0, None, 4, 1000, None) == EINVAL
+    assert f(FAKE_A, None, 1024, 0, None, 4, 1000, None) == EINVAL
+    assert f(FAKE_A, FAKE_B, 999, 0, None, 4, 1000, None) == EINVAL       # ld < P
+    assert f(FAKE_A, FAKE_B, 0, 100, None, 4, 1000, None) == EINVAL       # tile width not a power of two
+    assert f(FAKE_A, FAKE_B, 1024, 0, None, 0, 1000, None) == EINVAL
+    assert f(FAKE_A, FAKE_B, 1024, 0, None, 129, 1000, None) == ERANGE    # beyond the held array
+    assert f(FAKE_A, FAKE_B, 1024, 0, None, 2000, 1000, None) == ERANGE
+    header = open(os.path.join(ROOT, "include", "combo.h")).read()
+    assert re.search(r"#define\s+COMBO_DIVERGENCE_NOALLOC_MAX_WORKERS\s+128\b", header)
+
+
 def test_hashed_round_argument_errors(L):
     f = L.combo_round_hashed
 
