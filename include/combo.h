@@ -16,8 +16,13 @@
  *     synchronises: work is enqueued on `stream` (a hipStream_t passed as void*;
  *     NULL = the default stream) and the call returns at once.  The caller owns every
  *     buffer and must keep it alive until the stream has passed the enqueued work.
- *   - Return value: COMBO_OK (0) or a negative combo_status.  On an error nothing has
- *     been enqueued.  No exceptions, no aborts.
+ *   - Return value: COMBO_OK (0) or a negative combo_status.  No exceptions, no aborts.
+ *     COMBO_EINVAL, COMBO_EALIAS and COMBO_ERANGE are found before anything is enqueued.
+ *     COMBO_EHIP is what the HIP runtime reports when a launch is enqueued; a call that
+ *     enqueues several kernels (the separate-pass form of the local steps, the divergence
+ *     monitor) may then have enqueued the earlier ones, so after COMBO_EHIP the contents
+ *     of the output - and of d_src where a call is documented to step it in place - are
+ *     unspecified.
  *   - Parameter matrices are row-major float32 [N][ld]: worker w's parameter e is at
  *     index w*ld + e, e in [0, P).  ld >= P is the row pitch in elements.  The padding
  *     columns [P, ld) are never read and never written.
@@ -118,8 +123,9 @@ int combo_peer_in_degree(int32_t* d_degree, const int32_t* d_peers, int32_t N, i
  *   d_peers  in,  device, int32[N*S*R]; may be NULL when R == 0 (the round is a copy).
  * Errors: COMBO_EINVAL for N < 1, S < 1, S > P, R < 0, R > N-1, ld < P, a NULL d_dst or
  * d_src, NULL d_peers with R > 0; COMBO_EALIAS if [d_dst, d_dst + N*ld) overlaps
- * [d_src, d_src + N*ld) (a worker would read a neighbour's already aggregated values);
- * COMBO_ERANGE if N*ceil(P/tile) exceeds the grid limit of 2^31-1 workgroups.
+ * [d_src, d_src + N*ld) (a worker would read a neighbour's already aggregated values) or
+ * the table, the dataset sizes or (dynamic rounds) the status array; COMBO_ERANGE if
+ * N*ceil(P/tile) exceeds the grid limit of 2^31-1 workgroups or N*ld*4 does not fit in 64 bits.
  */
 int combo_segment_gossip_round(float* d_dst, const float* d_src, int64_t ld,
                                const int32_t* d_peers, const float* d_dataset_sizes,
@@ -235,6 +241,32 @@ int combo_local_sgd_steps_then_gossip_tiled(float* d_dst, const float* d_src, co
                                             void* stream);
 
 /*
+ * A round that reads one layout and writes another (Eq. 4's reassembly lands directly in
+ * the layout the caller wants next): the work of combo_local_sgd_steps_then_gossip (tau = 0:
+ * of combo_segment_gossip_round; with d_status: of combo_segment_gossip_round_dynamic) with
+ * independent layouts for the front buffer and the back buffer.  A caller whose models are
+ * row-major enters the tiled arena with its first round and leaves it with its last one,
+ * without a combo_pack_tiled / combo_unpack_tiled pass.  Same arithmetic, order and
+ * results as the single-layout entry points, bit for bit.
+ *   d_dst, dst_ld, dst_tile_cols   back buffer: dst_tile_cols == 0: row-major [N][dst_ld];
+ *                                  else tiled [T][N][dst_tile_cols] (dst_ld ignored)
+ *   d_src, src_ld, src_tile_cols   front buffer, likewise; never modified
+ *   d_grads                        tau matrices in the FRONT buffer's layout, back to back;
+ *                                  may be NULL when tau == 0
+ *   d_status                       NULL, or dynamic-worker status (then tau must be 0)
+ * Always runs the LDS-slab kernel with one strip per tile.  Errors: COMBO_EINVAL / COMBO_EALIAS
+ * as for the single-layout calls; COMBO_ERANGE when that kernel cannot be used: buffers not
+ * 16-byte aligned, a row pitch that is not a multiple of 4, two tiled sides of different
+ * tile widths, N rows of a tile (or, with two row-major sides, of 64 columns) not fitting in
+ * 64 KiB of LDS, or d_status together with tau > 0.
+ */
+int combo_round_relayout(float* d_dst, int64_t dst_ld, int32_t dst_tile_cols, const float* d_src,
+                         int64_t src_ld, int32_t src_tile_cols, const float* d_grads, int32_t tau,
+                         float lr, const int32_t* d_peers, const float* d_dataset_sizes,
+                         const uint8_t* d_status, int32_t N, int64_t P, int32_t S, int32_t R,
+                         void* stream);
+
+/*
  * A whole iteration in ONE launch, without a peer table: peer selection exactly as
  * combo_make_peer_table(seed, round) would make it (every workgroup draws the peer lists
  * it needs from the counter-based hash while its loads are in flight), the optional tau
@@ -311,6 +343,9 @@ int combo_aggregation_divergence_noalloc(double* d_dist2, const float* d_x, int6
  *                          row-tile kernel; 2: same as 0
  *   COMBO_TUNE_SLAB_COLS   strip width of the slab kernel: 0 = automatic, or a power of
  *                          two in [64, 1024] (ignored if that slab does not fit in LDS)
+ *   COMBO_TUNE_SLAB_ORDER  slab kernel: 0: workgroup i works on strip i (consecutive strips go
+ *                          round-robin to the 8 XCDs); 1: every XCD works through its own
+ *                          contiguous eighth of the strips
  *   COMBO_TUNE_TILE_COLS   row-tile kernel: columns of one worker handled by one
  *                          workgroup: 0 = automatic (2048, or 1024 for more than 384
  *                          workers), or 1024, 2048, 4096
@@ -326,7 +361,8 @@ enum {
     COMBO_TUNE_XCD_SWIZZLE = 1,
     COMBO_TUNE_FUSED_MODE = 2,
     COMBO_TUNE_KERNEL = 3,
-    COMBO_TUNE_SLAB_COLS = 4
+    COMBO_TUNE_SLAB_COLS = 4,
+    COMBO_TUNE_SLAB_ORDER = 5
 };
 int combo_tune(int key, int value);
 /* Which kernel the row-major aggregation entry points use for N workers and R replicas

@@ -86,20 +86,44 @@ class GossipArena:
         return dst
 
     # ---- one synchronisation round ---------------------------------------------------
-    def step(self, grads=None, lr=0.0, status=None):
-        """Peer table of the current round, then the aggregation (after the tau local SGD
-        steps with `grads`, shape (tau,) + front.shape, if given), then swap.  `status`
-        (uint8[N]: 0 offline, 1 active, 2 newcomer) selects the dynamic-worker semantics."""
-        N, P, S, R = self.N, self.P, self.S, self.R
+    def _make_table(self, status):
+        N, S, R = self.N, self.S, self.R
         if status is not None:
-            if grads is not None:
-                raise ValueError("dynamic workers and fused local steps cannot be combined")
             _b.make_peer_table_dynamic(self.peers, status, N, S, R, self.seed, self.round)
         elif self.selection == "pooled":
             _b.make_peer_table_pooled(self.peers, N, S, R, self.seed, self.round)
         else:
             _b.make_peer_table(self.peers, N, S, R, self.seed, self.round)
-        peers = self.peers if R > 0 else None
+        return self.peers if R > 0 else None
+
+    def step_in(self, rows, grads=None, lr=0.0, status=None):
+        """A round whose front buffer is the caller's row-major (N, ld) tensor `rows` (and
+        row-major gradients (tau, N, ld)): the result lands in the arena's own layout, so a
+        tiled arena is entered without a separate conversion pass."""
+        peers = self._make_table(status)
+        _b.round_relayout(self.back, self.tile_cols, rows, 0, peers, self.N, self.P, self.S, self.R,
+                          grads=grads, lr=lr, dataset_sizes=self.dataset_sizes, status=status)
+        self._cur = 1 - self._cur
+        self.round += 1
+        return self
+
+    def step_out(self, out_rows, grads=None, lr=0.0, status=None):
+        """A round from the arena's front buffer into the caller's row-major (N, ld) tensor
+        `out_rows` (gradients in the arena's layout).  The arena's own buffers are unchanged."""
+        peers = self._make_table(status)
+        _b.round_relayout(out_rows, 0, self.front, self.tile_cols, peers, self.N, self.P, self.S, self.R,
+                          grads=grads, lr=lr, dataset_sizes=self.dataset_sizes, status=status)
+        self.round += 1
+        return out_rows
+
+    def step(self, grads=None, lr=0.0, status=None):
+        """Peer table of the current round, then the aggregation (after the tau local SGD
+        steps with `grads`, shape (tau,) + front.shape, if given), then swap.  `status`
+        (uint8[N]: 0 offline, 1 active, 2 newcomer) selects the dynamic-worker semantics."""
+        N, P, S, R = self.N, self.P, self.S, self.R
+        if status is not None and grads is not None:
+            raise ValueError("dynamic workers and fused local steps cannot be combined")
+        peers = self._make_table(status)
         d = self.dataset_sizes
         if self.layout == "tiled":
             if grads is not None:

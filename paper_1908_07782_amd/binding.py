@@ -12,8 +12,9 @@ TUNE_XCD_SWIZZLE = 1
 TUNE_FUSED_MODE = 2
 TUNE_KERNEL = 3
 TUNE_SLAB_COLS = 4
+TUNE_SLAB_ORDER = 5
 
-EXPORTS = ("combo_aggregation_divergence_noalloc", "combo_round_hashed", "combo_round_kernel_kind", "combo_aggregation_divergence_tiled", "combo_tiled_cols", "combo_tiled_elems", "combo_pack_tiled", "combo_unpack_tiled",
+EXPORTS = ("combo_round_relayout", "combo_aggregation_divergence_noalloc", "combo_round_hashed", "combo_round_kernel_kind", "combo_aggregation_divergence_tiled", "combo_tiled_cols", "combo_tiled_elems", "combo_pack_tiled", "combo_unpack_tiled",
            "combo_segment_gossip_round_tiled", "combo_local_sgd_steps_then_gossip_tiled",
            "combo_local_sgd_steps_then_gossip", "combo_aggregation_divergence", "combo_aggregation_divergence_workspace",
            "combo_make_peer_table_dynamic", "combo_segment_gossip_round_dynamic",
@@ -83,6 +84,9 @@ def lib():
         L.combo_aggregation_divergence_tiled.restype = ctypes.c_int
         L.combo_aggregation_divergence_noalloc.argtypes = [vp, vp, i64, i32, vp, i32, i64, vp]
         L.combo_aggregation_divergence_noalloc.restype = ctypes.c_int
+        L.combo_round_relayout.argtypes = [vp, i64, i32, vp, i64, i32, vp, i32, f32, vp, vp, vp, i32, i64,
+                                           i32, i32, vp]
+        L.combo_round_relayout.restype = ctypes.c_int
         L.combo_round_hashed.argtypes = [vp, vp, vp, i32, f32, i64, i32, vp, i32, i64, i32, i32, u64, u64, vp]
         L.combo_round_hashed.restype = ctypes.c_int
         L.combo_round_kernel_kind.argtypes = [i32, i32]
@@ -139,6 +143,23 @@ def _matrix(t, name):
     return t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1])
 
 
+def _check_round_inputs(peers, dataset_sizes, status, N, S, R, device):
+    """Host-side size checks of the small device inputs of a round: a short or strided
+    table, dataset-size or status array would be an out-of-bounds device read."""
+    if R > 0 and (peers is None or not peers.is_cuda or peers.dtype != torch.int32
+                  or not peers.is_contiguous() or peers.numel() < N * S * R):
+        raise ValueError("peers: need a contiguous int32 device tensor with N*S*R entries")
+    if dataset_sizes is not None and (not dataset_sizes.is_cuda or dataset_sizes.dtype != torch.float32
+                                      or not dataset_sizes.is_contiguous() or dataset_sizes.numel() < N):
+        raise ValueError("dataset_sizes: need a contiguous float32 device tensor with N entries")
+    if status is not None and (not status.is_cuda or status.dtype != torch.uint8
+                               or not status.is_contiguous() or status.numel() < N):
+        raise ValueError("status: need a contiguous uint8 device tensor with N entries")
+    for name, t in (("peers", peers if R > 0 else None), ("dataset_sizes", dataset_sizes), ("status", status)):
+        if t is not None and t.device != device:
+            raise ValueError(f"{name}: lives on {t.device}, the parameters on {device}")
+
+
 def make_peer_table(peers, N, S, R, seed, rnd, stream=None):
     """combo_make_peer_table: fills the int32 device tensor `peers` (N*S*R entries)."""
     if R > 0 and (peers is None or peers.numel() < N * S * R or not peers.is_contiguous()):
@@ -167,6 +188,7 @@ def peer_in_degree(degree, peers, N, S, R, stream=None):
     """combo_peer_in_degree: degree (int32[N], device) <- serve load of the table."""
     if degree.numel() < N or not degree.is_contiguous():
         raise ValueError("degree: need a contiguous int32 device tensor with N entries")
+    _check_round_inputs(peers, None, None, N, S, R, degree.device)
     rc = lib().combo_peer_in_degree(_dev_ptr(degree, torch.int32, "degree"),
                                     _dev_ptr(peers, torch.int32, "peers", optional=(R == 0)),
                                     N, S, R, _stream_ptr(stream))
@@ -179,8 +201,9 @@ def make_peer_table_dynamic(peers, status, N, S, R, seed, rnd, stream=None):
     """combo_make_peer_table_dynamic: status is a uint8 device tensor of N entries."""
     if R > 0 and (peers is None or peers.numel() < N * S * R or not peers.is_contiguous()):
         raise ValueError("peers: need a contiguous int32 device tensor with N*S*R entries")
-    if status.numel() < N or not status.is_contiguous():
-        raise ValueError("status: need a contiguous uint8 device tensor with N entries")
+    if status is None:
+        raise ValueError("status is required")
+    _check_round_inputs(peers, None, status, N, S, R, status.device)
     rc = lib().combo_make_peer_table_dynamic(_dev_ptr(peers, torch.int32, "peers", optional=(R == 0)),
                                              _dev_ptr(status, torch.uint8, "status"), N, S, R,
                                              ctypes.c_uint64(seed), ctypes.c_uint64(rnd),
@@ -196,8 +219,9 @@ def segment_gossip_round_dynamic(dst, src, peers, status, P, S, R, dataset_sizes
     ld = _matrix(src, "src")
     if _matrix(dst, "dst") != ld or dst.shape[0] != N:
         raise ValueError("dst must have src's row count and pitch")
-    if status.numel() < N or not status.is_contiguous():
-        raise ValueError("status: need a contiguous uint8 device tensor with N entries")
+    if status is None:
+        raise ValueError("status is required")
+    _check_round_inputs(peers, dataset_sizes, status, N, S, R, src.device)
     rc = lib().combo_segment_gossip_round_dynamic(
         _dev_ptr(dst, torch.float32, "dst"), _dev_ptr(src, torch.float32, "src"), ld,
         _dev_ptr(peers, torch.int32, "peers", optional=(R == 0)),
@@ -225,6 +249,7 @@ def aggregation_divergence(dist2, x, P, workspace, dataset_sizes=None, stream=No
         raise ValueError("dist2: need a contiguous float64 device tensor with N entries")
     if not (workspace.is_cuda and workspace.is_contiguous()):
         raise ValueError("workspace: need a contiguous device tensor")
+    _check_round_inputs(None, dataset_sizes, None, N, 1, 0, x.device)
     rc = lib().combo_aggregation_divergence(
         _dev_ptr(dist2, torch.float64, "dist2"), _dev_ptr(x, torch.float32, "x"), ld,
         _dev_ptr(dataset_sizes, torch.float32, "dataset_sizes", optional=True), N, P,
@@ -241,6 +266,7 @@ def segment_gossip_round(dst, src, peers, P, S, R, dataset_sizes=None, stream=No
     ld = _matrix(src, "src")
     if _matrix(dst, "dst") != ld or dst.shape[0] != N:
         raise ValueError("dst must have src's row count and pitch")
+    _check_round_inputs(peers, dataset_sizes, None, N, S, R, src.device)
     rc = lib().combo_segment_gossip_round(
         _dev_ptr(dst, torch.float32, "dst"), _dev_ptr(src, torch.float32, "src"), ld,
         _dev_ptr(peers, torch.int32, "peers", optional=(R == 0)),
@@ -258,6 +284,7 @@ def local_sgd_then_gossip(dst, src, grad, lr, peers, P, S, R, dataset_sizes=None
     if _matrix(dst, "dst") != ld or _matrix(grad, "grad") != ld or dst.shape[0] != N \
             or grad.shape[0] != N:
         raise ValueError("dst and grad must have src's row count and pitch")
+    _check_round_inputs(peers, dataset_sizes, None, N, S, R, src.device)
     rc = lib().combo_local_sgd_then_gossip(
         _dev_ptr(dst, torch.float32, "dst"), _dev_ptr(src, torch.float32, "src"),
         _dev_ptr(grad, torch.float32, "grad"), ctypes.c_float(lr), ld,
@@ -281,6 +308,7 @@ def local_sgd_steps_then_gossip(dst, src, grads, lr, peers, P, S, R, dataset_siz
                         and (N == 1 or grads.stride(1) == ld)
                         and (tau == 1 or grads.stride(0) == N * ld)):
         raise ValueError("grads: need (tau, N, .) float32 with src's pitch and slice stride N*ld")
+    _check_round_inputs(peers, dataset_sizes, None, N, S, R, src.device)
     rc = lib().combo_local_sgd_steps_then_gossip(
         _dev_ptr(dst, torch.float32, "dst"), _dev_ptr(src, torch.float32, "src"),
         _dev_ptr(grads, torch.float32, "grads") if tau > 0 else None, tau, ctypes.c_float(lr), ld,
@@ -337,6 +365,7 @@ def unpack_tiled(rows, tiled, N, P, tile_cols, stream=None):
 def segment_gossip_round_tiled(dst, src, tile_cols, peers, N, P, S, R, dataset_sizes=None,
                                status=None, stream=None):
     n = tiled_elems(N, P, tile_cols)
+    _check_round_inputs(peers, dataset_sizes, status, N, S, R, src.device)
     rc = lib().combo_segment_gossip_round_tiled(
         _flat(dst, n, "dst"), _flat(src, n, "src"), tile_cols,
         _dev_ptr(peers, torch.int32, "peers", optional=(R == 0)),
@@ -350,6 +379,7 @@ def segment_gossip_round_tiled(dst, src, tile_cols, peers, N, P, S, R, dataset_s
 def local_sgd_steps_then_gossip_tiled(dst, src, grads, tau, lr, tile_cols, peers, N, P, S, R,
                                       dataset_sizes=None, stream=None):
     n = tiled_elems(N, P, tile_cols)
+    _check_round_inputs(peers, dataset_sizes, None, N, S, R, src.device)
     rc = lib().combo_local_sgd_steps_then_gossip_tiled(
         _flat(dst, n, "dst"), _flat(src, n, "src"),
         _flat(grads, n * tau, "grads") if tau > 0 else None, tau, ctypes.c_float(lr), tile_cols,
@@ -365,6 +395,9 @@ def aggregation_divergence_tiled(dist2, x, tile_cols, N, P, workspace, dataset_s
     """combo_aggregation_divergence_tiled: x is a flat tiled buffer [T][N][tile_cols]."""
     if dist2.numel() < N or not dist2.is_contiguous():
         raise ValueError("dist2: need a contiguous float64 device tensor with N entries")
+    if not (workspace.is_cuda and workspace.is_contiguous()):
+        raise ValueError("workspace: need a contiguous device tensor")
+    _check_round_inputs(None, dataset_sizes, None, N, 1, 0, x.device)
     rc = lib().combo_aggregation_divergence_tiled(
         _dev_ptr(dist2, torch.float64, "dist2"), _flat(x, tiled_elems(N, P, tile_cols), "x"), tile_cols,
         _dev_ptr(dataset_sizes, torch.float32, "dataset_sizes", optional=True), N, P,
@@ -380,8 +413,7 @@ def aggregation_divergence_noalloc(dist2, x, N, P, tile_cols=0, dataset_sizes=No
     argument.  tile_cols == 0: x is an (N, ld)-strided matrix; else a flat tiled buffer."""
     if dist2.numel() < N or not dist2.is_contiguous():
         raise ValueError("dist2: need a contiguous float64 device tensor with N entries")
-    if dataset_sizes is not None and (dataset_sizes.numel() < N or not dataset_sizes.is_contiguous()):
-        raise ValueError("dataset_sizes: need a contiguous float32 device tensor with N entries")
+    _check_round_inputs(None, dataset_sizes, None, N, 1, 0, x.device)
     if tile_cols:
         ld, px = 0, _flat(x, tiled_elems(N, P, tile_cols), "x")
     else:
@@ -397,11 +429,48 @@ def aggregation_divergence_noalloc(dist2, x, N, P, tile_cols=0, dataset_sizes=No
     return dist2
 
 
+def round_relayout(dst, dst_tile_cols, src, src_tile_cols, peers, N, P, S, R, *, grads=None, lr=0.0,
+                   dataset_sizes=None, status=None, stream=None):
+    """combo_round_relayout: a round from one layout into another.  A side with tile_cols == 0
+    is an (N, ld)-strided matrix, else a flat tiled buffer; grads (tau, ...) has src's layout."""
+    tau = 0 if grads is None else int(grads.shape[0])
+    _check_round_inputs(peers, dataset_sizes, status, N, S, R, dst.device)
+
+    def side(t, tile, name):
+        if tile:
+            return _flat(t, tiled_elems(N, P, tile), name), 0
+        if t.shape[0] != N:
+            raise ValueError(f"{name}: need N rows")
+        return _dev_ptr(t, torch.float32, name), _matrix(t, name)
+
+    pd, dst_ld = side(dst, dst_tile_cols, "dst")
+    ps, src_ld = side(src, src_tile_cols, "src")
+    pg = None
+    if tau:
+        if src_tile_cols:
+            pg = _flat(grads.reshape(-1), tiled_elems(N, P, src_tile_cols) * tau, "grads")
+        else:
+            if not (grads.dim() == 3 and grads.shape[1] == N and grads.stride(2) == 1
+                    and (N == 1 or grads.stride(1) == src_ld) and (tau == 1 or grads.stride(0) == N * src_ld)):
+                raise ValueError("grads: need (tau, N, .) float32 with src's pitch and slice stride N*ld")
+            pg = _dev_ptr(grads, torch.float32, "grads")
+    rc = lib().combo_round_relayout(pd, dst_ld, dst_tile_cols, ps, src_ld, src_tile_cols, pg, tau,
+                                    ctypes.c_float(lr),
+                                    _dev_ptr(peers, torch.int32, "peers", optional=(R == 0)),
+                                    _dev_ptr(dataset_sizes, torch.float32, "dataset_sizes", optional=True),
+                                    _dev_ptr(status, torch.uint8, "status", optional=True),
+                                    N, P, S, R, _stream_ptr(stream))
+    if rc:
+        raise ComboError(rc, "combo_round_relayout")
+    return dst
+
+
 def round_hashed(dst, src, N, P, S, R, seed, rnd, *, grads=None, lr=0.0, tile_cols=0,
                  dataset_sizes=None, stream=None):
     """combo_round_hashed: peer selection + optional local steps + aggregation in one
     launch.  Row-major: dst/src are (N, ld)-strided, grads (tau, N, ld); tiled: flat buffers."""
     tau = 0 if grads is None else int(grads.shape[0])
+    _check_round_inputs(None, dataset_sizes, None, N, S, 0, src.device)
     if tile_cols:
         n = tiled_elems(N, P, tile_cols)
         ld = tile_cols

@@ -14,12 +14,28 @@ std::atomic<int> g_swizzle{1};
 std::atomic<int> g_fused_mode{0};
 std::atomic<int> g_kernel{0};
 std::atomic<int> g_slab_cols{0};
+std::atomic<int> g_slab_order{0};             // 0: strip i to workgroup i; 1: contiguous strips per XCD
 
 enum PlanKind { kPlanTile = 0, kPlanSlab = 1 };
 struct Plan {
     PlanKind kind;
     int cols;      // strip width for the slab kernels
 };
+
+// where a parameter matrix lives: row-major [N][ld] (tile == 0) or tiled [T][N][tile]
+struct Layout {
+    int64_t ld;
+    int tile;
+};
+
+// the slab kernels' grid: one workgroup per strip, rounded up to a multiple of 8
+constexpr uint64_t kMaxStrips = 0x7FFFFFF0ull;
+
+int log2_of(int pow2) {
+    int k = 0;
+    while ((1 << k) < pow2) ++k;
+    return k;
+}
 
 bool overlaps(const void* a, uint64_t a_bytes, const void* b, uint64_t b_bytes) {
     const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
@@ -34,8 +50,19 @@ int check_round_args(const float* dst, const float* src, int64_t ld, const int32
     if (N < 1 || S < 1 || P < 1 || (int64_t)S > P || R < 0 || R > N - 1) return COMBO_EINVAL;
     if (ld < P || dst == nullptr || src == nullptr) return COMBO_EINVAL;
     if (R > 0 && peers == nullptr) return COMBO_EINVAL;
+    if ((uint64_t)ld > (UINT64_MAX / sizeof(float)) / (uint64_t)N) return COMBO_ERANGE;   // N*ld*4 overflows
     const uint64_t bytes = (uint64_t)N * (uint64_t)ld * sizeof(float);
     if (overlaps(dst, bytes, src, bytes)) return COMBO_EALIAS;
+    return COMBO_OK;
+}
+
+// the small inputs of a round (table, dataset sizes, status) must not lie inside the back buffer
+int check_small_inputs(const float* dst, uint64_t dst_bytes, const int32_t* peers, const float* dsz,
+                       const uint8_t* status, int32_t N, int32_t S, int32_t R) {
+    const uint64_t table_bytes = (uint64_t)N * (uint64_t)S * (uint64_t)R * sizeof(int32_t);
+    if (peers != nullptr && table_bytes != 0 && overlaps(dst, dst_bytes, peers, table_bytes)) return COMBO_EALIAS;
+    if (dsz != nullptr && overlaps(dst, dst_bytes, dsz, (uint64_t)N * sizeof(float))) return COMBO_EALIAS;
+    if (status != nullptr && overlaps(dst, dst_bytes, status, (uint64_t)N)) return COMBO_EALIAS;
     return COMBO_OK;
 }
 
@@ -61,7 +88,8 @@ int row_tile_cols(int32_t N, int64_t P) {
 int enqueue_round(float* dst, const float* src, const float* grad, float lr, int64_t ld,
                   const int32_t* peers, const float* dsz, int32_t N, int64_t P, int32_t S,
                   int32_t R, Plan plan, hipStream_t st, const uint8_t* status = nullptr,
-                  int32_t tau = 1, int arena_tile = 0, bool hashed = false, uint64_t hash_sr = 0) {
+                  int32_t tau = 1, int arena_tile = 0, bool hashed = false, uint64_t hash_sr = 0,
+                  const Layout* dst_layout = nullptr) {
     const int tile_cols = row_tile_cols(N, P);
     const bool swizzle = g_swizzle.load() != 0;
     combo::RoundArgs a;
@@ -86,9 +114,23 @@ int enqueue_round(float* dst, const float* src, const float* grad, float lr, int
     a.tile_shift = 0;
     a.grad_slice = (int64_t)N * ld;
     if (arena_tile) {         // tiled arena [T][N][Wt]
-        while ((1 << a.tile_shift) < arena_tile) ++a.tile_shift;
+        a.tile_shift = log2_of(arena_tile);
         const int64_t tiles = (P + arena_tile - 1) / arena_tile;
         a.grad_slice = tiles * (int64_t)N * (int64_t)arena_tile;
+    }
+    a.dst_ld = ld;            // the back buffer normally has the front buffer's layout
+    a.dst_tile_shift = a.tile_shift;
+    if (dst_layout != nullptr) {
+        a.dst_ld = dst_layout->ld;
+        a.dst_tile_shift = dst_layout->tile ? log2_of(dst_layout->tile) : 0;
+    }
+    a.nstrips = 0;
+    a.strips_per_xcd = 0;
+    if (plan.kind == kPlanSlab) {
+        const uint64_t strips = ((uint64_t)P + (uint64_t)plan.cols - 1) / (uint64_t)plan.cols;
+        if (strips > kMaxStrips) return COMBO_ERANGE;
+        a.nstrips = (uint32_t)strips;
+        if (g_slab_order.load() == 1) a.strips_per_xcd = (a.nstrips + combo::kXcds - 1) / combo::kXcds;
     }
     a.hash_sr = hash_sr;
     if (hashed)
@@ -111,7 +153,7 @@ Plan plan_for(const float* dst, const float* src, const float* grad, int64_t ld,
     if (want == 1) return tile;
     if (!(aligned16(dst) && aligned16(src) && aligned16(grad) && ld % 4 == 0)) return tile;
     const int W = combo::slab_strip_cols(N, R, g_slab_cols.load());
-    if (W == 0 || ((uint64_t)P + (uint64_t)W - 1) / (uint64_t)W > 0x7FFFFFFFull) return tile;
+    if (W == 0 || ((uint64_t)P + (uint64_t)W - 1) / (uint64_t)W > kMaxStrips) return tile;
     return Plan{kPlanSlab, W};
 }
 
@@ -155,7 +197,9 @@ int combo_peer_in_degree(int32_t* d_degree, const int32_t* d_peers, int32_t N, i
 int combo_segment_gossip_round(float* d_dst, const float* d_src, int64_t ld,
                                const int32_t* d_peers, const float* d_dataset_sizes, int32_t N,
                                int64_t P, int32_t S, int32_t R, void* stream) {
-    const int rc = check_round_args(d_dst, d_src, ld, d_peers, N, P, S, R);
+    int rc = check_round_args(d_dst, d_src, ld, d_peers, N, P, S, R);
+    if (rc == COMBO_OK)
+        rc = check_small_inputs(d_dst, (uint64_t)N * (uint64_t)ld * 4, d_peers, d_dataset_sizes, nullptr, N, S, R);
     if (rc != COMBO_OK) return rc;
     const Plan plan = plan_for(d_dst, d_src, nullptr, ld, N, P, R);
     return enqueue_round(d_dst, d_src, nullptr, 0.0f, ld, d_peers, d_dataset_sizes, N, P, S, R, plan,
@@ -177,9 +221,11 @@ int combo_segment_gossip_round_dynamic(float* d_dst, const float* d_src, int64_t
                                        const int32_t* d_peers, const float* d_dataset_sizes,
                                        const uint8_t* d_status, int32_t N, int64_t P, int32_t S,
                                        int32_t R, void* stream) {
-    const int rc = check_round_args(d_dst, d_src, ld, d_peers, N, P, S, R);
+    int rc = check_round_args(d_dst, d_src, ld, d_peers, N, P, S, R);
     if (rc != COMBO_OK) return rc;
     if (d_status == nullptr) return COMBO_EINVAL;
+    rc = check_small_inputs(d_dst, (uint64_t)N * (uint64_t)ld * 4, d_peers, d_dataset_sizes, d_status, N, S, R);
+    if (rc != COMBO_OK) return rc;
     const Plan plan = plan_for(d_dst, d_src, nullptr, ld, N, P, R);
     if (plan.kind == kPlanTile && ((uint64_t)P + 1023) / 1024 * (uint64_t)N > 0x7FFFFFFFull)
         return COMBO_ERANGE;
@@ -191,13 +237,16 @@ int combo_local_sgd_steps_then_gossip(float* d_dst, float* d_src, const float* d
                                       float lr, int64_t ld, const int32_t* d_peers,
                                       const float* d_dataset_sizes, int32_t N, int64_t P, int32_t S,
                                       int32_t R, void* stream) {
-    const int rc = check_round_args(d_dst, d_src, ld, d_peers, N, P, S, R);
+    int rc = check_round_args(d_dst, d_src, ld, d_peers, N, P, S, R);
     if (rc != COMBO_OK) return rc;
     if (tau < 0 || (tau > 0 && d_grads == nullptr)) return COMBO_EINVAL;
     const uint64_t bytes = (uint64_t)N * (uint64_t)ld * sizeof(float);
+    if (tau > 0 && bytes > UINT64_MAX / (uint64_t)tau) return COMBO_ERANGE;
     if (tau > 0 && (overlaps(d_grads, bytes * (uint64_t)tau, d_src, bytes) ||
                     overlaps(d_grads, bytes * (uint64_t)tau, d_dst, bytes)))
         return COMBO_EALIAS;
+    rc = check_small_inputs(d_dst, bytes, d_peers, d_dataset_sizes, nullptr, N, S, R);
+    if (rc != COMBO_OK) return rc;
     const hipStream_t st = (hipStream_t)stream;
     const Plan plan = plan_for(d_dst, d_src, d_grads, ld, N, P, R);
     if (tau == 0)   // no local step: the plain round
@@ -249,7 +298,7 @@ int check_tiled_args(const float* dst, const float* src, int32_t tile_cols, cons
     const uint64_t bytes = (uint64_t)tiled_elems(N, P, tile_cols) * sizeof(float);
     if (overlaps(dst, bytes, src, bytes)) return COMBO_EALIAS;
     if (combo::slab_strip_cols(N, R, tile_cols) != tile_cols) return COMBO_ERANGE;   // slab too big
-    if (((uint64_t)P + (uint64_t)tile_cols - 1) / (uint64_t)tile_cols > 0x7FFFFFFFull)
+    if (((uint64_t)P + (uint64_t)tile_cols - 1) / (uint64_t)tile_cols > kMaxStrips)
         return COMBO_ERANGE;
     return COMBO_OK;
 }
@@ -302,7 +351,10 @@ int combo_segment_gossip_round_tiled(float* d_dst, const float* d_src, int32_t t
                                      const int32_t* d_peers, const float* d_dataset_sizes,
                                      const uint8_t* d_status, int32_t N, int64_t P, int32_t S,
                                      int32_t R, void* stream) {
-    const int rc = check_tiled_args(d_dst, d_src, tile_cols, d_peers, N, P, S, R);
+    int rc = check_tiled_args(d_dst, d_src, tile_cols, d_peers, N, P, S, R);
+    if (rc == COMBO_OK)
+        rc = check_small_inputs(d_dst, (uint64_t)tiled_elems(N, P, tile_cols) * 4, d_peers, d_dataset_sizes,
+                                d_status, N, S, R);
     if (rc != COMBO_OK) return rc;
     return enqueue_round(d_dst, d_src, nullptr, 0.0f, tile_cols, d_peers, d_dataset_sizes, N, P, S, R,
                          Plan{kPlanSlab, tile_cols}, (hipStream_t)stream, d_status, 1, tile_cols);
@@ -312,7 +364,10 @@ int combo_local_sgd_steps_then_gossip_tiled(float* d_dst, const float* d_src, co
                                             int32_t tau, float lr, int32_t tile_cols,
                                             const int32_t* d_peers, const float* d_dataset_sizes,
                                             int32_t N, int64_t P, int32_t S, int32_t R, void* stream) {
-    const int rc = check_tiled_args(d_dst, d_src, tile_cols, d_peers, N, P, S, R);
+    int rc = check_tiled_args(d_dst, d_src, tile_cols, d_peers, N, P, S, R);
+    if (rc == COMBO_OK)
+        rc = check_small_inputs(d_dst, (uint64_t)tiled_elems(N, P, tile_cols) * 4, d_peers, d_dataset_sizes,
+                                nullptr, N, S, R);
     if (rc != COMBO_OK) return rc;
     if (tau < 0 || (tau > 0 && (d_grads == nullptr || !aligned16(d_grads)))) return COMBO_EINVAL;
     const uint64_t bytes = (uint64_t)tiled_elems(N, P, tile_cols) * sizeof(float);
@@ -322,6 +377,47 @@ int combo_local_sgd_steps_then_gossip_tiled(float* d_dst, const float* d_src, co
     return enqueue_round(d_dst, d_src, tau > 0 ? d_grads : nullptr, lr, tile_cols, d_peers,
                          d_dataset_sizes, N, P, S, R, Plan{kPlanSlab, tile_cols}, (hipStream_t)stream,
                          nullptr, tau, tile_cols);
+}
+
+int combo_round_relayout(float* d_dst, int64_t dst_ld, int32_t dst_tile_cols, const float* d_src,
+                         int64_t src_ld, int32_t src_tile_cols, const float* d_grads, int32_t tau,
+                         float lr, const int32_t* d_peers, const float* d_dataset_sizes,
+                         const uint8_t* d_status, int32_t N, int64_t P, int32_t S, int32_t R,
+                         void* stream) {
+    if (N < 1 || S < 1 || P < 1 || (int64_t)S > P || R < 0 || R > N - 1) return COMBO_EINVAL;
+    if (d_dst == nullptr || d_src == nullptr || (R > 0 && d_peers == nullptr)) return COMBO_EINVAL;
+    if (tau < 0 || (tau > 0 && d_grads == nullptr)) return COMBO_EINVAL;
+    if (src_tile_cols != 0 && !tile_cols_ok(src_tile_cols)) return COMBO_EINVAL;
+    if (dst_tile_cols != 0 && !tile_cols_ok(dst_tile_cols)) return COMBO_EINVAL;
+    if (src_tile_cols == 0 && src_ld < P) return COMBO_EINVAL;
+    if (dst_tile_cols == 0 && dst_ld < P) return COMBO_EINVAL;
+    if (d_status != nullptr && tau > 0) return COMBO_ERANGE;   // no kernel folds steps into a dynamic round
+    // one strip of the slab kernel = one tile of the tiled side(s)
+    if (src_tile_cols != 0 && dst_tile_cols != 0 && src_tile_cols != dst_tile_cols) return COMBO_ERANGE;
+    if ((src_tile_cols == 0 && ((uint64_t)src_ld > (UINT64_MAX / 4) / (uint64_t)N || src_ld % 4 != 0)) ||
+        (dst_tile_cols == 0 && ((uint64_t)dst_ld > (UINT64_MAX / 4) / (uint64_t)N || dst_ld % 4 != 0)))
+        return COMBO_ERANGE;
+    if (!aligned16(d_dst) || !aligned16(d_src) || !aligned16(d_grads)) return COMBO_ERANGE;
+    const int tile = src_tile_cols != 0 ? src_tile_cols : dst_tile_cols;
+    const int W = combo::slab_strip_cols(N, R, tile ? tile : g_slab_cols.load());
+    if (W == 0 || (tile != 0 && W != tile)) return COMBO_ERANGE;          // slab does not fit in LDS
+    if (((uint64_t)P + (uint64_t)W - 1) / (uint64_t)W > kMaxStrips) return COMBO_ERANGE;
+    const uint64_t src_bytes = 4 * (src_tile_cols ? (uint64_t)tiled_elems(N, P, src_tile_cols)
+                                                  : (uint64_t)N * (uint64_t)src_ld);
+    const uint64_t dst_bytes = 4 * (dst_tile_cols ? (uint64_t)tiled_elems(N, P, dst_tile_cols)
+                                                  : (uint64_t)N * (uint64_t)dst_ld);
+    if (overlaps(d_dst, dst_bytes, d_src, src_bytes)) return COMBO_EALIAS;
+    if (tau > 0 && src_bytes > UINT64_MAX / (uint64_t)tau) return COMBO_ERANGE;
+    if (tau > 0 && (overlaps(d_grads, src_bytes * (uint64_t)tau, d_src, src_bytes) ||
+                    overlaps(d_grads, src_bytes * (uint64_t)tau, d_dst, dst_bytes)))
+        return COMBO_EALIAS;
+    const int rc = check_small_inputs(d_dst, dst_bytes, d_peers, d_dataset_sizes, d_status, N, S, R);
+    if (rc != COMBO_OK) return rc;
+    const Layout dst_layout{dst_tile_cols ? (int64_t)dst_tile_cols : dst_ld, dst_tile_cols};
+    return enqueue_round(d_dst, d_src, tau > 0 ? d_grads : nullptr, lr,
+                         src_tile_cols ? (int64_t)src_tile_cols : src_ld, d_peers, d_dataset_sizes, N, P,
+                         S, R, Plan{kPlanSlab, W}, (hipStream_t)stream, d_status, tau, src_tile_cols,
+                         false, 0, &dst_layout);
 }
 
 int combo_round_hashed(float* d_dst, const float* d_src, const float* d_grads, int32_t tau, float lr,
@@ -345,7 +441,7 @@ int combo_round_hashed(float* d_dst, const float* d_src, const float* d_grads, i
         if (W == 0 || ld % 4 != 0) return COMBO_ERANGE;
     }
     if (!aligned16(d_dst) || !aligned16(d_src) || !aligned16(d_grads)) return COMBO_ERANGE;
-    if (((uint64_t)P + (uint64_t)W - 1) / (uint64_t)W > 0x7FFFFFFFull) return COMBO_ERANGE;
+    if (((uint64_t)P + (uint64_t)W - 1) / (uint64_t)W > kMaxStrips) return COMBO_ERANGE;
     const uint64_t bytes = elems * sizeof(float);
     if (overlaps(d_dst, bytes, d_src, bytes)) return COMBO_EALIAS;
     if (tau > 0 && (overlaps(d_grads, bytes * (uint64_t)tau, d_src, bytes) ||
@@ -474,6 +570,10 @@ int combo_tune(int key, int value) {
                 return COMBO_EINVAL;
             g_slab_cols.store(value);
             return COMBO_OK;
+        case COMBO_TUNE_SLAB_ORDER:
+            if (value != 0 && value != 1) return COMBO_EINVAL;
+            g_slab_order.store(value);
+            return COMBO_OK;
         default:
             return COMBO_EINVAL;
     }
@@ -486,6 +586,7 @@ int combo_get_tune(int key) {
         case COMBO_TUNE_FUSED_MODE: return g_fused_mode.load();
         case COMBO_TUNE_KERNEL: return g_kernel.load();
         case COMBO_TUNE_SLAB_COLS: return g_slab_cols.load();
+        case COMBO_TUNE_SLAB_ORDER: return g_slab_order.load();
         default: return COMBO_EINVAL;
     }
 }

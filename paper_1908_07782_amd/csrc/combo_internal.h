@@ -29,7 +29,12 @@ struct RoundArgs {
     float lr;                // learning rate of the fused local step
     int32_t tau;             // number of fused local steps (gradient slices)
     int64_t grad_slice;      // elements between consecutive gradient slices
-    int32_t tile_shift;      // 0: row-major [N][ld]; else log2(Wt) of the tiled layout [T][N][Wt]
+    int32_t tile_shift;      // front buffer and gradients: 0: row-major [N][ld]; else log2(Wt) of the tiled layout [T][N][Wt]
+    int64_t dst_ld;          // back buffer: its own pitch and layout (normally the front buffer's)
+    int32_t dst_tile_shift;
+    uint32_t nstrips;        // slab kernels: ceil(P / strip width)
+    uint32_t strips_per_xcd; // slab kernels: 0: workgroup i takes strip i; else workgroup i takes strip
+                             // (i mod 8)*strips_per_xcd + i/8, a contiguous range of strips per XCD
     uint64_t hash_sr;        // table-free rounds: peer-hash state after seed and round
 };
 
@@ -82,6 +87,7 @@ hipError_t launch_round_slab_hashed(const RoundArgs& a, int strip_cols, hipStrea
 hipError_t launch_round_slab_dynamic(const RoundArgs& a, int strip_cols, uint32_t grid, size_t lds,
                                      hipStream_t st);
 size_t slab_lds_bytes(int32_t N, int32_t R, int strip_cols, bool hashed);
+uint32_t slab_grid(const RoundArgs& a, int strip_cols);
 int slab_threads(int32_t N, int strip_cols);
 
 // number of workgroups launch_round would use, or 0 if that exceeds the grid limit

@@ -59,11 +59,18 @@ int slab_strip_cols(int32_t N, int32_t R, int requested, bool hashed) {
     return slab_lds_bytes(N, R, 64, hashed) <= kLimit ? 64 : 0;
 }
 
-hipError_t launch_round_slab(const RoundArgs& a, int W, hipStream_t st) {
+// workgroups of a slab launch: one per strip, or, with a contiguous range of strips per XCD,
+// 8 * strips_per_xcd (the surplus ones return at once); 0: beyond the grid limit
+uint32_t slab_grid(const RoundArgs& a, int W) {
     const uint64_t strips = ((uint64_t)a.P + (uint64_t)W - 1) / (uint64_t)W;
-    if (strips > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    if (strips > 0x7FFFFFF0ull || strips != a.nstrips) return 0;
+    return a.strips_per_xcd != 0 ? (uint32_t)kXcds * a.strips_per_xcd : a.nstrips;
+}
+
+hipError_t launch_round_slab(const RoundArgs& a, int W, hipStream_t st) {
+    const uint32_t grid = slab_grid(a, W);
+    if (grid == 0) return hipErrorInvalidValue;
     const size_t lds = slab_lds_bytes(a.N, a.R, W, false);
-    const uint32_t grid = (uint32_t)strips;
     if (a.status != nullptr) return launch_round_slab_dynamic(a, W, grid, lds, st);
     switch (a.R) {
         case 0: return launch_rt<0>(a, W, grid, lds, st);

@@ -113,7 +113,9 @@ constexpr int kMaxHashedR = 8;   // replica counts the in-kernel peer draw suppo
 // Fisher-Yates shuffle of the N-1 other workers, on a virtual array whose displaced
 // slots (at most one per step) are kept in registers.  Same picks, same order as the
 // peer-table kernel.  h_sr = hash state after seed and round.
-// swap partner of shuffle step j for (w, s): j + reduce(hash(seed, round, w, s, j), N-1-j)
+//   shuffle_partner      swap partner of step j: j + reduce(hash(seed, round, w, s, j), N-1-j)
+//   picks_from_partners  the picks given the R partners (pure integer bookkeeping)
+//   draw_peers           both, for one (w, s)
 __device__ __forceinline__ int32_t shuffle_partner(uint64_t h_sr, int32_t w, int32_t s, int32_t j,
                                                    int32_t N) {
     const uint64_t h = hash_take_in(hash_take_in(h_sr, (uint64_t)w), (uint64_t)s);
@@ -121,7 +123,6 @@ __device__ __forceinline__ int32_t shuffle_partner(uint64_t h_sr, int32_t w, int
     return j + (int32_t)(((word >> 32) * (uint64_t)(uint32_t)(N - 1 - j)) >> 32);
 }
 
-// the picks given the R swap partners (partner[j] for step j): pure integer bookkeeping
 __device__ __forceinline__ void picks_from_partners(const int32_t* partner, int32_t w, int32_t R,
                                                     int32_t (&out)[kMaxHashedR]) {
     int32_t pos[kMaxHashedR], val[kMaxHashedR];
@@ -144,25 +145,11 @@ __device__ __forceinline__ void picks_from_partners(const int32_t* partner, int3
 
 __device__ __forceinline__ void draw_peers(uint64_t h_sr, int32_t w, int32_t s, int32_t N, int32_t R,
                                            int32_t (&out)[kMaxHashedR]) {
-    const uint64_t h = hash_take_in(hash_take_in(h_sr, (uint64_t)w), (uint64_t)s);
-    const int32_t M = N - 1;
-    int32_t pos[kMaxHashedR], val[kMaxHashedR];
+    int32_t partner[kMaxHashedR];
 #pragma unroll
-    for (int j = 0; j < kMaxHashedR; ++j) {
-        if (j < R) {
-            const uint64_t word = hash_take_in(h, (uint64_t)j);
-            const int32_t r = j + (int32_t)(((word >> 32) * (uint64_t)(uint32_t)(M - j)) >> 32);
-            int32_t at_r = r, at_j = j;              // current contents of slots r and j
-#pragma unroll
-            for (int k = 0; k < j; ++k) {            // the latest displacement of a slot wins
-                if (pos[k] == r) at_r = val[k];
-                if (pos[k] == j) at_j = val[k];
-            }
-            out[j] = at_r + (at_r >= w ? 1 : 0);     // skip over w itself
-            pos[j] = r;                              // slot r now holds what slot j held
-            val[j] = at_j;
-        }
-    }
+    for (int j = 0; j < kMaxHashedR; ++j)
+        if (j < R) partner[j] = shuffle_partner(h_sr, w, s, j, N);
+    picks_from_partners(partner, w, R, out);
 }
 
 // segment of column e: floor(e / L), the last segment also owning the remainder (Eq. 1)
@@ -175,11 +162,21 @@ __device__ __forceinline__ int32_t segment_of(int64_t e, const RoundArgs& a) {
 
 // Index of worker `row`'s column e.  Row-major: row*ld + e.  Tiled [T][N][Wt]: tile
 // e / Wt holds Wt consecutive columns of all N workers, worker-major inside the tile.
+// The front buffer (with the gradients) and the back buffer each have their own layout.
+__device__ __forceinline__ size_t layout_offset(int64_t ld, int32_t tile_shift, int32_t N, int32_t row,
+                                                int64_t e) {
+    if (tile_shift == 0) return (size_t)row * (size_t)ld + (size_t)e;
+    const size_t tile = (size_t)e >> tile_shift;
+    const size_t in_tile = (size_t)e & (((size_t)1 << tile_shift) - 1);
+    return ((tile * (size_t)N + (size_t)row) << tile_shift) + in_tile;
+}
+
 __device__ __forceinline__ size_t elem_offset(const RoundArgs& a, int32_t row, int64_t e) {
-    if (a.tile_shift == 0) return (size_t)row * (size_t)a.ld + (size_t)e;
-    const size_t tile = (size_t)e >> a.tile_shift;
-    const size_t in_tile = (size_t)e & (((size_t)1 << a.tile_shift) - 1);
-    return ((tile * (size_t)a.N + (size_t)row) << a.tile_shift) + in_tile;
+    return layout_offset(a.ld, a.tile_shift, a.N, row, e);
+}
+
+__device__ __forceinline__ size_t elem_offset_dst(const RoundArgs& a, int32_t row, int64_t e) {
+    return layout_offset(a.dst_ld, a.dst_tile_shift, a.N, row, e);
 }
 
 // pre-aggregation value of worker `row` at column e: the stored parameter, or, when the
@@ -224,7 +221,7 @@ __device__ __forceinline__ void average_element(const RoundArgs& a, int32_t w, i
         }
         out = __fdiv_rn(num, den);
     }
-    a.dst[elem_offset(a, w, e)] = out;
+    a.dst[elem_offset_dst(a, w, e)] = out;
 }
 
 // Eq. (3) with dynamic workers (Sec. 4.2) for one element.  status: 0 offline (keeps its
@@ -261,7 +258,7 @@ __device__ __forceinline__ void average_element_dynamic(const RoundArgs& a, int3
     }
     float out = own;
     if (cnt > 0) out = WEIGHTED ? __fdiv_rn(acc, den) : __fmul_rn(acc, __fdiv_rn(1.0f, (float)cnt));
-    a.dst[elem_offset(a, w, e)] = out;
+    a.dst[elem_offset_dst(a, w, e)] = out;
 }
 
 }  // namespace combo

@@ -161,8 +161,44 @@ def test_round_argument_errors(L):
     assert call(dst=ctypes.c_void_p(0x20000000 + 4 * 1024 * 4 - 4), src=FAKE_B) == EALIAS
     assert call(dst=ctypes.c_void_p(0x20000000 - 4 * 1024 * 4 + 4), src=FAKE_B) == EALIAS
     # grid limit: N * ceil(P / tile) must stay below 2^31
-    assert f(FAKE_A, ctypes.c_void_p(0x7000000000000000), 1 << 40, FAKE_T, None, 16384, 1 << 40, 4, 2,
+    low = ctypes.c_void_p(0x1000)                 # a table below the (huge) back buffer
+    assert f(FAKE_A, ctypes.c_void_p(0x7000000000000000), 1 << 40, low, None, 16384, 1 << 40, 4, 2,
              None) == ERANGE
+    # the table, the dataset sizes (and the status array) must not lie inside the back buffer
+    assert call(peers=ctypes.c_void_p(0x10000000 + 64)) == EALIAS
+    assert call(d=ctypes.c_void_p(0x10000000 + 4 * 1024 * 4 - 4)) == EALIAS
+    g = L.combo_segment_gossip_round_dynamic
+    assert g(FAKE_A, FAKE_B, 1024, FAKE_T, None, ctypes.c_void_p(0x10000000 + 100), 4, 1000, 4, 2, None) == EALIAS
+    # N * ld * 4 beyond 64 bits
+    assert f(FAKE_A, FAKE_B, 1 << 61, low, None, 8, 1000, 4, 2, None) == ERANGE
+
+
+def test_relayout_argument_errors(L):
+    f = L.combo_round_relayout
+    f.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64,
+                  ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p,
+                  ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32,
+                  ctypes.c_int32, ctypes.c_void_p]
+
+    def call(dst=FAKE_A, dst_ld=1024, dst_tile=0, src=FAKE_B, src_ld=1024, src_tile=64, grads=None, tau=0,
+             peers=FAKE_T, status=None, N=4, P=1000, S=4, R=2):
+        return f(dst, dst_ld, dst_tile, src, src_ld, src_tile, grads, tau, 0.1, peers, None, status, N, P, S,
+                 R, None)
+
+    assert call(N=0) == EINVAL and call(S=1001) == EINVAL and call(R=4) == EINVAL
+    assert call(dst=None) == EINVAL and call(src=None) == EINVAL and call(peers=None) == EINVAL
+    assert call(tau=1) == EINVAL and call(tau=-1) == EINVAL
+    assert call(src_tile=100) == EINVAL and call(dst_tile=7) == EINVAL
+    assert call(dst_ld=999) == EINVAL                               # row-major side: pitch below P
+    assert call(src_tile=0, src_ld=999) == EINVAL
+    assert call(dst_tile=128) == ERANGE                             # two tiled sides of different widths
+    assert call(dst_ld=1001, P=1001, S=4) == ERANGE                 # pitch not a multiple of 4
+    assert call(dst=ctypes.c_void_p(0x10000004)) == ERANGE          # not 16-byte aligned
+    assert call(N=300, R=2, src_tile=64) == ERANGE                  # slab does not fit
+    assert call(status=FAKE_C, grads=FAKE_C, tau=1) == ERANGE
+    assert call(dst=FAKE_B) == EALIAS
+    assert call(grads=FAKE_B, tau=1) == EALIAS
+    assert call(peers=ctypes.c_void_p(0x10000000 + 16)) == EALIAS
 
 
 def test_fused_argument_errors(L):
