@@ -33,46 +33,20 @@ def kernel_source_digest():
 
 
 def recorded_traffic(workload, layout):
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc
-    summary, or None when there is none or the kernel source changed since."""
+    """(HBM bytes per launch of the dominant kernel, the file they come from): the committed
+    rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE, scaled by a copy of known size), or
+    (None, None) when there is none or the kernel sources changed since it was taken."""
     tag = "" if layout == "rows" else "_tiled"
-    path = os.path.join(ROOT, "profiles", f"gossip_slab_kernel_{workload}{tag}_pmc.txt")
+    name = f"profiles/gossip_slab_kernel_{workload}{tag}_pmc.txt"
+    path = os.path.join(ROOT, name)
     if not os.path.exists(path):
-        return None
+        return None, None
     text = open(path).read()
     m = re.search(r"^kernel_source_digest:\s*(\w+)", text, flags=re.M)
     t = re.search(r"^hbm_bytes_per_launch:\s*([0-9.eE+]+)", text, flags=re.M)
     if not m or not t or m.group(1) != kernel_source_digest():
-        return None
-    return float(t.group(1))
-
-
-def cpu_baseline(wl, X0_host, budget_s=15.0):
-    """The oracle as it stands (single thread), timed on whole rounds of the same
-    workload until about `budget_s` seconds of CPU work are spent."""
-    import numpy as np
-    from oracle import ref
-    X = X0_host
-    Y = np.empty_like(X)
-    G = None
-    if wl.fused:
-        G = (np.random.default_rng(1).standard_normal(X.shape, dtype=np.float32) * wl.grad_std)
-    t0 = time.perf_counter()
-    rounds = 0
-    while True:
-        ph = ref.make_peer_table(wl.N, wl.S, wl.R, wl.hash_seed, rounds)
-        if wl.fused:
-            Y = ref.local_sgd_then_gossip(X, G, wl.lr, ph, wl.P, wl.S, wl.R)
-        else:
-            ref.gossip_round(X, ph, wl.P, wl.S, wl.R, out=Y)
-        X, Y = Y, X
-        rounds += 1
-        dt = time.perf_counter() - t0
-        if dt >= budget_s:
-            break
-    return {"value": rounds / dt, "unit": "rounds/s", "cores": 1, "kind": "oracle",
-            "sample": f"{rounds} full rounds of {wl.name} (all N={wl.N} workers, all P={wl.P} "
-                      f"columns), single thread, {dt:.1f} s"}
+        return None, None
+    return float(t.group(1)), name
 
 
 def time_kernel(fn, stream, reps=20, warm=3):
@@ -157,19 +131,65 @@ def extras(combo, wl):
         rec.update(kw)
         print(json.dumps(rec), flush=True)
 
-    # practical ceilings on this device for the same footprint: a plain device-to-device copy
-    # and the library's own round with R = 0 (a copy through the slab kernel), both layouts
-    emit("torch copy_ of one arena half (ceiling probe)", time_kernel(
+    # practical ceilings on this device for the same footprint: gather-free passes with the
+    # kernels' access patterns (combo_bandwidth_probe), torch's own copy, and the library's
+    # round with R = 0 (a copy through the slab kernel), both layouts
+    foot = N * ld * 4
+    for flight in (1, 2, 4, 8):
+        emit(f"probe: flat copy, {flight} x 128-bit words in flight per thread", time_kernel(
+            lambda: combo.bandwidth_probe(combo.PROBE_COPY, arena[1], arena[0], P, param=flight, stream=stream),
+            stream), 2 * foot, note="bytes = read + write")
+    for flight in (4, 8):
+        emit(f"probe: read only, {flight} words in flight", time_kernel(
+            lambda: combo.bandwidth_probe(combo.PROBE_READ, arena[1], arena[0], P, param=flight, stream=stream),
+            stream), foot, note="bytes = read")
+        emit(f"probe: write only, {flight} words in flight", time_kernel(
+            lambda: combo.bandwidth_probe(combo.PROBE_WRITE, arena[1], None, P, param=flight, stream=stream),
+            stream), foot, note="bytes = write")
+    wt0 = combo.tiled_cols(N, R)
+    widths = sorted({64, 128, 256, 512, 1024, wt0})
+    for cols in widths:
+        moved = 8 * N * (P // cols) * cols
+        emit(f"probe: row-chunk copy, N chunks of {cols} columns per workgroup (row-major footprint)",
+             time_kernel(lambda: combo.bandwidth_probe(combo.PROBE_ROW_CHUNKS, arena[1], arena[0], P, cols=cols,
+                                                       stream=stream), stream), moved, note="bytes = read + write")
+        emit(f"probe: tile copy, one contiguous N x {cols} tile per workgroup (tiled footprint)",
+             time_kernel(lambda: combo.bandwidth_probe(combo.PROBE_TILES, arena[1], arena[0], P, cols=cols,
+                                                       stream=stream), stream), moved, note="bytes = read + write")
+    for k in sorted({1, 3, R + 1}):
+        emit(f"probe: {k} read streams + 1 write stream, no reuse out of LDS (worker-major order)",
+             time_kernel(lambda: combo.bandwidth_probe(combo.PROBE_MULTI_READ, arena[1], arena[0], P, param=k,
+                                                       stream=stream), stream),
+             4 * (k + 1) * N * (P // 1024) * 1024, note="bytes = (k reads + 1 write) per element as issued")
+    emit("torch copy_ of one arena half", time_kernel(
         lambda: arena[1].copy_(arena[0]), stream), 8 * N * ld, note="bytes = read + write")
     emit("round with R=0, row-major (copy through the slab kernel)", time_kernel(
         lambda: combo.segment_gossip_round(arena[1], arena[0], None, P, S, 0, stream=stream), stream),
         8 * N * P, note="bytes = read + write")
-    wt0 = combo.tiled_cols(N, R)
     t0 = torch.zeros((2, combo.tiled_elems(N, P, wt0)), dtype=torch.float32, device="cuda")
     combo.pack_tiled(t0[0], arena[0], N, P, wt0)
     emit("round with R=0, tiled (copy through the slab kernel)", time_kernel(
         lambda: combo.segment_gossip_round_tiled(t0[1], t0[0], wt0, None, N, P, S, 0, stream=stream),
         stream), 8 * N * P, note="bytes = read + write", tiled_cols=wt0)
+    # the round itself, row-major, with the two strip orders (A/B in one process), and the
+    # rounds that change layout on the way (no pack / unpack pass)
+    combo.make_peer_table(peers, N, S, R, 0, 1)
+    for rep in range(2):
+        for order in (0, 1):
+            combo.tune(combo.TUNE_SLAB_ORDER, order)
+            emit(f"combo_segment_gossip_round, row-major, strip order {order} (pass {rep})", time_kernel(
+                lambda: combo.segment_gossip_round(arena[1], arena[0], peers, P, S, R, stream=stream), stream),
+                8 * N * P, note="bytes = compulsory read + write")
+            emit(f"combo_segment_gossip_round_tiled, strip order {order} (pass {rep})", time_kernel(
+                lambda: combo.segment_gossip_round_tiled(t0[1], t0[0], wt0, peers, N, P, S, R, stream=stream),
+                stream), 8 * N * P, note="bytes = compulsory read + write", tiled_cols=wt0)
+    combo.tune(combo.TUNE_SLAB_ORDER, 0)
+    emit("combo_round_relayout rows -> tiled", time_kernel(
+        lambda: combo.round_relayout(t0[1], wt0, arena[0], 0, peers, N, P, S, R, stream=stream), stream),
+        8 * N * P, note="bytes = compulsory read + write", tiled_cols=wt0)
+    emit("combo_round_relayout tiled -> rows", time_kernel(
+        lambda: combo.round_relayout(arena[1], 0, t0[0], wt0, peers, N, P, S, R, stream=stream), stream),
+        8 * N * P, note="bytes = compulsory read + write", tiled_cols=wt0)
     del t0
     emit("combo_make_peer_table", time_kernel(
         lambda: combo.make_peer_table(peers, N, S, R, 0, 1, stream=stream), stream))
@@ -251,16 +271,271 @@ def extras(combo, wl):
         del grads
 
 
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def host_memory_available():
+    try:
+        for line in open("/proc/meminfo"):
+            if line.startswith("MemAvailable"):
+                return int(line.split()[1]) * 1024
+    except OSError:
+        pass
+    return 0
+
+
+def to_host(dev_rows, out=None):
+    """(N, ld) device matrix -> numpy (N, ld), row by row (bounded staging memory)."""
+    import numpy as np
+    import torch
+    N, ld = dev_rows.shape
+    if out is None:
+        out = np.empty((N, ld), np.float32)
+    for w in range(N):
+        torch.from_numpy(out[w]).copy_(dev_rows[w])
+    return out
+
+
+def parity_windows(wl, budget_cols):
+    """Column windows for the sampled check of a round too large for the host: row start
+    and end, every segment boundary, the columns where the flat element offset crosses
+    2^31 and 2^32 in either layout, and seeded random ones up to `budget_cols` columns."""
+    import random
+    width = 4096
+    starts = {0, max(0, wl.P - width)}
+    L = wl.P // wl.S
+    for s in range(1, wl.S):
+        starts.add(max(0, s * L - width // 2))
+    rnd = random.Random(wl.P)
+    while len(starts) * width < budget_cols:
+        starts.add(rnd.randrange(0, max(1, wl.P - width)))
+    return [(c, min(width, wl.P - c)) for c in sorted(starts)]
+
+
+def check_against_oracle(combo, wl, rows, grad_rows, run_round_zero, budget_s):
+    """Parity of the timed kernel's first round with the CPU oracle, and the oracle's own
+    speed.  `rows` (device, (N, ld)) holds the initial parameters; run_round_zero() makes
+    the device run round 0 from them with the timed entry point and returns the result as a
+    row-major (N, ld) device matrix.  Returns (parity dict, cpu_baseline dict)."""
+    import numpy as np
+    from oracle import ref
+    N, P, S, R, ld = wl.N, wl.P, wl.S, wl.R, wl.ld
+    ph = ref.make_peer_table(N, S, R, wl.hash_seed, 0)
+    need = (3 if wl.fused else 2) * N * ld * 4 + 2 * ld * 4
+    full = need < 0.6 * host_memory_available()
+    got_dev, peers_dev = run_round_zero()
+    tables_ok = bool(np.array_equal(peers_dev.cpu().numpy()[:N * S * R].reshape(ph.shape), ph))
+    worst, bitwise, checked = 0.0, True, 0
+
+    def compare(got, want):
+        nonlocal worst, bitwise, checked
+        checked += want.size
+        if np.array_equal(got.view(np.uint32), want.view(np.uint32)):
+            return
+        bitwise = False
+        worst = max(worst, float(np.max(np.abs(got - want) / np.maximum(np.abs(want), 1e-30))))
+
+    cpu_s, cpu_rounds, cpu_cols = 0.0, 0, 0
+    if full:
+        Xh = to_host(rows)
+        Gh = to_host(grad_rows) if wl.fused else None
+        X, Y = Xh[:, :P], np.empty((N, ld), np.float32)[:, :P]
+        t0 = time.perf_counter()
+        if wl.fused:
+            Y = ref.local_sgd_then_gossip(X, Gh[:, :P], wl.lr, ph, P, S, R)
+        else:
+            ref.gossip_round(X, ph, P, S, R, out=Y)
+        cpu_s += time.perf_counter() - t0
+        cpu_rounds = 1
+        row = np.empty(ld, np.float32)
+        import torch
+        for w in range(N):
+            torch.from_numpy(row).copy_(got_dev[w])
+            compare(row[:P], Y[w])
+        # the oracle of record keeps going on whole rounds until the budget is spent
+        while cpu_s < budget_s:
+            X, Y = Y, X
+            ph_k = ref.make_peer_table(N, S, R, wl.hash_seed, cpu_rounds)
+            t0 = time.perf_counter()
+            if wl.fused:
+                Y = ref.local_sgd_then_gossip(X, Gh[:, :P], wl.lr, ph_k, P, S, R)
+            else:
+                ref.gossip_round(X, ph_k, P, S, R, out=Y)
+            cpu_s += time.perf_counter() - t0
+            cpu_rounds += 1
+        cpu = {"value": cpu_rounds / cpu_s, "unit": "rounds/s", "cores": 1, "kind": "oracle",
+               "sample": f"{cpu_rounds} full rounds of {wl.name} (all N={N} workers, all P={P} columns), "
+                         f"single thread, {cpu_s:.1f} s", "extrapolated": False}
+        mode = "every element of round 0"
+    else:
+        # too large for the host: column windows (a round is column-separable: output column e
+        # depends on input column e only), oracle timed on the same windows and scaled to P
+        wins = parity_windows(wl, budget_cols=1 << 22)
+        for c0, wd in wins:
+            Xw = np.ascontiguousarray(rows[:, c0:c0 + wd].cpu().numpy())
+            t0 = time.perf_counter()
+            if wl.fused:
+                Gw = np.ascontiguousarray(grad_rows[:, c0:c0 + wd].cpu().numpy())
+                want = ref.local_sgd_then_gossip(Xw, Gw, wl.lr, ph, P, S, R, col0=c0)
+            else:
+                want = ref.gossip_round(Xw, ph, P, S, R, col0=c0)
+            cpu_s += time.perf_counter() - t0
+            cpu_cols += wd
+            compare(np.ascontiguousarray(got_dev[:, c0:c0 + wd].cpu().numpy()), np.ascontiguousarray(want))
+        cpu = {"value": cpu_cols / cpu_s / P, "unit": "rounds/s", "cores": 1, "kind": "oracle",
+               "sample": f"{len(wins)} column windows of round 0 of {wl.name} ({cpu_cols} of {P} columns, all "
+                         f"N={N} workers), single thread, {cpu_s:.1f} s; scaled by P / columns",
+               "extrapolated": True}
+        mode = f"{len(wins)} column windows of round 0 (host memory too small for the whole arena)"
+    parity = {"tables_bit_exact": tables_ok, "bitwise_equal": bitwise, "max_rel_err": worst,
+              "elements_checked": checked, "columns_checked": checked // N, "of_columns": P,
+              "coverage": mode, "tolerance": 1e-6, "ok": bool(tables_ok and worst <= 1e-6)}
+    cpu["cpu_model"] = cpu_model()
+    cpu["host_cores_visible"] = os.cpu_count()
+    return parity, cpu
+
+
+def measure(combo, wl, args, layout, steps, warmup, trials, with_oracle, cpu_budget):
+    """One workload in one arena layout: parity of round 0 against the oracle (optional),
+    then `trials` timed runs of `steps` steps each.  Returns a dict of results."""
+    import torch
+    dev = torch.device("cuda:0")
+    N, P, S, R = wl.N, wl.P, wl.S, wl.R
+    is_tiled = layout == "tiled"
+    wt = (args.tiled_cols or combo.tiled_cols(N, R)) if is_tiled else 0
+    stream = torch.cuda.current_stream()
+    rows = torch.zeros((N, wl.ld), dtype=torch.float32, device=dev)
+    combo.workloads.fill_params(rows, wl)
+    grad_rows = None
+    if wl.fused:
+        grad_rows = torch.zeros((N, wl.ld), dtype=torch.float32, device=dev)
+        combo.workloads.fill_grads(grad_rows, wl, 0)
+    if is_tiled:
+        arena = torch.zeros((2, combo.tiled_elems(N, P, wt)), dtype=torch.float32, device=dev)
+        combo.pack_tiled(arena[0], rows, N, P, wt)
+        grads = None
+        if wl.fused:
+            grads = torch.zeros_like(arena[0])
+            combo.pack_tiled(grads, grad_rows, N, P, wt)
+    else:
+        arena = torch.zeros((2, N, wl.ld), dtype=torch.float32, device=dev)
+        arena[0].copy_(rows)
+        grads = grad_rows
+    peers = torch.empty(max(N * S * R, 1), dtype=torch.int32, device=dev)
+    state = {"cur": 0, "round": 0}
+    one_launch = bool(args.one_launch) and R <= 8 and (is_tiled or combo.round_kernel_kind(N, R) == 1)
+    g1 = None if grads is None else grads.reshape((1,) + tuple(grads.shape))
+
+    def step(ev=None):
+        cur, rnd = state["cur"], state["round"]
+        if one_launch:
+            if ev is not None:
+                ev[0].record(stream)
+            combo.round_hashed(arena[1 - cur], arena[cur], N, P, S, R, wl.hash_seed, rnd,
+                               grads=g1, lr=wl.lr, tile_cols=wt, stream=stream)
+            if ev is not None:
+                ev[1].record(stream)
+            state["cur"], state["round"] = 1 - cur, rnd + 1
+            return
+        combo.make_peer_table(peers, N, S, R, wl.hash_seed, rnd, stream=stream)
+        if ev is not None:
+            ev[0].record(stream)
+        if is_tiled and wl.fused:
+            combo.local_sgd_steps_then_gossip_tiled(arena[1 - cur], arena[cur], grads, 1, wl.lr, wt,
+                                                    peers, N, P, S, R, stream=stream)
+        elif is_tiled:
+            combo.segment_gossip_round_tiled(arena[1 - cur], arena[cur], wt, peers, N, P, S, R, stream=stream)
+        elif wl.fused:
+            combo.local_sgd_then_gossip(arena[1 - cur], arena[cur], grads, wl.lr, peers, P, S, R, stream=stream)
+        else:
+            combo.segment_gossip_round(arena[1 - cur], arena[cur], peers, P, S, R, stream=stream)
+        if ev is not None:
+            ev[1].record(stream)
+        state["cur"], state["round"] = 1 - cur, rnd + 1
+
+    res = {"workload": wl.name, "N": N, "P": P, "S": S, "R": R, "layout": layout, "tiled_cols": wt,
+           "fused_local_step": wl.fused, "one_launch_per_round": one_launch}
+    if with_oracle:
+        def run_round_zero():
+            if one_launch:
+                combo.make_peer_table(peers, N, S, R, wl.hash_seed, 0, stream=stream)   # for the table check
+            step()
+            out = arena[state["cur"]]
+            if is_tiled:
+                back = torch.empty((N, wl.ld), dtype=torch.float32, device=dev)
+                combo.unpack_tiled(back, out, N, P, wt)
+                out = back
+            torch.cuda.synchronize()
+            return out, peers
+        res["parity"], res["cpu_baseline"] = check_against_oracle(combo, wl, rows, grad_rows, run_round_zero,
+                                                                  cpu_budget)
+    del rows
+
+    for _ in range(warmup):
+        step()
+    runs = []
+    for _ in range(trials):
+        events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                  for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(steps):
+            step(events[k])
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        runs.append((t1 - t0, sorted(a.elapsed_time(b) for a, b in events)))
+    runs.sort(key=lambda r: r[0])
+    wall, kern_ms = runs[len(runs) // 2]                 # the median trial
+    res["trial_rounds_per_s"] = sorted(steps / r[0] for r in runs)
+    res["rounds_per_s"] = steps / wall
+    res["ms_per_step"] = wall / steps * 1e3
+    kern_avg_ms = sum(kern_ms) / len(kern_ms)
+    slab = is_tiled or combo.round_kernel_kind(N, R) == 1
+    fused_in_kernel = wl.fused and (is_tiled or one_launch or
+                                    (slab and combo.get_tune(combo.TUNE_FUSED_MODE) == 0))
+    two_pass = wl.fused and not fused_in_kernel
+    # bytes that have to cross the HBM interface per launch: every element read once and
+    # written once (+ the gradient when the local step is folded in); the R further reads of
+    # an output are LDS reads.  The row-tile kernel re-reads provider rows out of L2.
+    hbm_bytes = 8 * N * P + (4 * N * P if fused_in_kernel else 0)
+    # (R+1) served values read + 1 written per element, + the gradient read of the local step
+    alg_bytes = wl.algorithmic_bytes_per_round + (4 * N * P if wl.fused else 0)
+    traffic, source = recorded_traffic(wl.name, layout)
+    res["kernel"] = ("gossip_slab_kernel" if slab else "gossip_round_kernel") + \
+        (" (after sgd_step_kernel)" if two_pass else "")
+    res["kernel_ms_avg"] = kern_avg_ms
+    res["kernel_ms_median"] = kern_ms[len(kern_ms) // 2]
+    res["kernel_ms_min"] = kern_ms[0]
+    res["hbm_bytes_per_launch"] = hbm_bytes
+    res["algorithmic_bytes_per_launch"] = alg_bytes
+    res["traffic"], res["traffic_source"] = traffic, source
+    res["hbm_gbs"] = (traffic or hbm_bytes) / (kern_avg_ms * 1e-3) / 1e9
+    res["hbm_frac"] = res["hbm_gbs"] / HBM_PEAK_GBS
+    res["effective_gbs"] = alg_bytes / (kern_avg_ms * 1e-3) / 1e9
+    res["bandwidth_meaningful"] = 8 * N * P > 512 * 1024 * 1024   # below: the arena sits in cache
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c2_resnet18")
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--trials", type=int, default=3,
+                    help="timed runs of --steps steps each; the line reports the median run")
+    ap.add_argument("--workload", default="c5_bertlarge")
     ap.add_argument("--tile", type=int, default=0, help="override COMBO_TUNE_TILE_COLS")
     ap.add_argument("--swizzle", type=int, default=-1, help="override COMBO_TUNE_XCD_SWIZZLE")
     ap.add_argument("--kernel", type=int, default=-1, help="override COMBO_TUNE_KERNEL")
     ap.add_argument("--slab-cols", type=int, default=-1, help="override COMBO_TUNE_SLAB_COLS")
+    ap.add_argument("--slab-order", type=int, default=-1, help="override COMBO_TUNE_SLAB_ORDER")
     ap.add_argument("--fused-mode", type=int, default=-1, help="override COMBO_TUNE_FUSED_MODE")
     ap.add_argument("--replicas", type=int, default=-1,
                     help="override R (0 turns the round into a plain copy of known size: the "
@@ -268,21 +543,23 @@ def main():
     ap.add_argument("--layout", choices=["rows", "tiled"], default="tiled",
                     help="arena layout: tiled [T][N][Wt] (default, the faster one) or row-major "
                          "[N][ld]")
-    ap.add_argument("--no-other-layout", action="store_true",
-                    help="skip the short side measurement of the other arena layout")
+    ap.add_argument("--no-per-config", action="store_true",
+                    help="skip the table of all five configurations (both layouts)")
     ap.add_argument("--one-launch", type=int, default=0,
                     help="0 (default): combo_make_peer_table, then the table-driven round; 1: a step is "
                          "ONE combo_round_hashed launch (peer selection inside the kernel; faster only "
                          "for launch-bound sizes)")
     ap.add_argument("--shape", default="", help="ad-hoc workload N,P,S,R instead of a named one")
     ap.add_argument("--tiled-cols", type=int, default=0, help="tile width of the tiled layout")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true",
+                    help="skip the oracle: no parity field and no cpu_baseline (profiling runs)")
     ap.add_argument("--cpu-budget", type=float, default=15.0,
                     help="seconds of CPU work for the oracle baseline (whole rounds)")
     ap.add_argument("--sweep-paper", action="store_true",
                     help="instead of the benchmark line: the paper's R and S sweeps (30 workers)")
     ap.add_argument("--extras", action="store_true",
-                    help="instead of the benchmark line: timings of the other entry points")
+                    help="instead of the benchmark line: bandwidth probes and timings of the other "
+                         "entry points")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (all N simulated workers live in one "
@@ -301,6 +578,8 @@ def main():
         combo.tune(combo.TUNE_KERNEL, args.kernel)
     if args.slab_cols >= 0:
         combo.tune(combo.TUNE_SLAB_COLS, args.slab_cols)
+    if args.slab_order >= 0:
+        combo.tune(combo.TUNE_SLAB_ORDER, args.slab_order)
     if args.fused_mode >= 0:
         combo.tune(combo.TUNE_FUSED_MODE, args.fused_mode)
     wl = combo.workloads.WORKLOADS[args.workload]
@@ -310,153 +589,87 @@ def main():
     if args.replicas >= 0:
         import dataclasses
         wl = dataclasses.replace(wl, R=args.replicas, name=f"{wl.name}_R{args.replicas}")
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
+    torch.cuda.set_device(0)
     if args.sweep_paper:
         return sweep_paper(combo, wl.P, args.layout)
     if args.extras:
         return extras(combo, wl)
 
-    rows = torch.zeros((wl.N, wl.ld), dtype=torch.float32, device=dev)
-    combo.workloads.fill_params(rows, wl)
-    X0_host = None
-    if not args.no_cpu_baseline:
-        X0_host = rows[:, :wl.P].cpu().numpy()
-    peers = torch.empty(max(wl.N * wl.S * wl.R, 1), dtype=torch.int32, device=dev)
-    stream = torch.cuda.current_stream()
+    oracle = not args.no_cpu_baseline
+    head = measure(combo, wl, args, args.layout, args.steps, args.warmup, args.trials, oracle,
+                   args.cpu_budget)
+    torch.cuda.empty_cache()
+    per_config = []
+    if not args.no_per_config:
+        # every configuration in both layouts (the headline one only in its other layout), short
+        # runs; parity of round 0 against the oracle on the whole arena where the host holds it
+        short = min(args.steps, 30)
+        for name, w in combo.workloads.WORKLOADS.items():
+            for layout in ("tiled", "rows"):
+                if name == wl.name and layout == args.layout:
+                    continue
+                r = measure(combo, w, args, layout, short, 3, args.trials,
+                            oracle and name != wl.name and layout == "tiled", 0.0)
+                r.pop("cpu_baseline", None)
+                r["steps"] = short
+                per_config.append(r)
+                torch.cuda.empty_cache()
 
-    used = {}
-
-    def run_layout(layout, steps, warmup):
-        """Time `steps` steps in one arena layout; returns (wall seconds, kernel ms list, Wt)."""
-        is_tiled = layout == "tiled"
-        wt = (args.tiled_cols or combo.tiled_cols(wl.N, wl.R)) if is_tiled else 0
-        if is_tiled:
-            arena = torch.zeros((2, combo.tiled_elems(wl.N, wl.P, wt)), dtype=torch.float32, device=dev)
-            combo.pack_tiled(arena[0], rows, wl.N, wl.P, wt)
-        else:
-            arena = torch.zeros((2, wl.N, wl.ld), dtype=torch.float32, device=dev)
-            arena[0].copy_(rows)
-        grads = None
-        if wl.fused:
-            grads = torch.zeros_like(arena[0])
-            grads.normal_(0.0, wl.grad_std)          # layout-agnostic: i.i.d. values
-        state = {"cur": 0, "round": 0}
-
-        one_launch = bool(args.one_launch) and wl.R <= 8 and \
-            (is_tiled or combo.round_kernel_kind(wl.N, wl.R) == 1)
-        used["one_launch"] = one_launch
-        g1 = None if grads is None else grads.reshape((1,) + tuple(grads.shape))
-
-        def step(ev=None):
-            cur, rnd = state["cur"], state["round"]
-            if one_launch:
-                if ev is not None:
-                    ev[0].record(stream)
-                combo.round_hashed(arena[1 - cur], arena[cur], wl.N, wl.P, wl.S, wl.R, wl.hash_seed, rnd,
-                                   grads=g1, lr=wl.lr, tile_cols=wt, stream=stream)
-                if ev is not None:
-                    ev[1].record(stream)
-                state["cur"], state["round"] = 1 - cur, rnd + 1
-                return
-            combo.make_peer_table(peers, wl.N, wl.S, wl.R, wl.hash_seed, rnd, stream=stream)
-            if ev is not None:
-                ev[0].record(stream)
-            if is_tiled and wl.fused:
-                combo.local_sgd_steps_then_gossip_tiled(arena[1 - cur], arena[cur], grads, 1, wl.lr, wt,
-                                                        peers, wl.N, wl.P, wl.S, wl.R, stream=stream)
-            elif is_tiled:
-                combo.segment_gossip_round_tiled(arena[1 - cur], arena[cur], wt, peers, wl.N, wl.P,
-                                                 wl.S, wl.R, stream=stream)
-            elif wl.fused:
-                combo.local_sgd_then_gossip(arena[1 - cur], arena[cur], grads, wl.lr, peers, wl.P,
-                                            wl.S, wl.R, stream=stream)
-            else:
-                combo.segment_gossip_round(arena[1 - cur], arena[cur], peers, wl.P, wl.S, wl.R,
-                                           stream=stream)
-            if ev is not None:
-                ev[1].record(stream)
-            state["cur"], state["round"] = 1 - cur, rnd + 1
-
-        for _ in range(warmup):
-            step()
-        events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-                  for _ in range(steps)]
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for k in range(steps):
-            step(events[k])
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        return t1 - t0, sorted(a.elapsed_time(b) for a, b in events), wt
-
-    tiled = args.layout == "tiled"
-    wall, kern_ms, Wt = run_layout(args.layout, args.steps, args.warmup)
-    one_launch = used["one_launch"]
-    other = None
-    if not args.no_other_layout:
-        other_name = "rows" if tiled else "tiled"
-        o_wall, o_ms, o_wt = run_layout(other_name, min(args.steps, 20), 3)
-        other = {"layout": other_name, "tiled_cols": o_wt, "rounds_per_s": min(args.steps, 20) / o_wall,
-                 "kernel_ms_avg": sum(o_ms) / len(o_ms)}
-    del rows
-
-    kern_avg_ms = sum(kern_ms) / len(kern_ms)
-    # (R+1) served values read + 1 written per element; the fused local step adds the
-    # read of the gradient (folded into the slab fill) or, in two passes, a read of x and
-    # g and a write of x
-    alg_bytes = wl.algorithmic_bytes_per_round
-    if wl.fused:
-        fused_in_kernel = tiled or one_launch or (combo.round_kernel_kind(wl.N, wl.R) == 1 and
-                                                  combo.get_tune(combo.TUNE_FUSED_MODE) == 0)
-        alg_bytes += 4 * wl.N * wl.P * (1 if fused_in_kernel else 3)
-    achieved = alg_bytes / (kern_avg_ms * 1e-3) / 1e9
-    slab = tiled or combo.round_kernel_kind(wl.N, wl.R) == 1
-    two_pass = wl.fused and not tiled and not one_launch and \
-        (not slab or combo.get_tune(combo.TUNE_FUSED_MODE) == 1)
-    kernel_name = ("gossip_slab_kernel" if slab else "gossip_round_kernel") + \
-        (" (+ sgd_step_kernel)" if two_pass else "")
     out = {
         "metric": "gossip rounds/sec and effective HBM GB/s (% of peak) at N workers x P params",
-        "value": args.steps / wall,
+        "value": head["rounds_per_s"],
         "unit": "rounds/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": wall / args.steps * 1e3,
+        "ms_per_step": head["ms_per_step"],
+        "trials": args.trials,
+        "trial_values": head["trial_rounds_per_s"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": wl.name, "N": wl.N, "P": wl.P, "S": wl.S, "R": wl.R,
-                   "fused_local_step": wl.fused, "one_launch_per_round": one_launch, "layout": args.layout, "tiled_cols": Wt, "kernel": combo.get_tune(combo.TUNE_KERNEL),
+                   "fused_local_step": wl.fused, "one_launch_per_round": head["one_launch_per_round"],
+                   "layout": args.layout, "tiled_cols": head["tiled_cols"],
+                   "kernel": combo.get_tune(combo.TUNE_KERNEL),
                    "slab_cols": combo.get_tune(combo.TUNE_SLAB_COLS),
+                   "slab_order": combo.get_tune(combo.TUNE_SLAB_ORDER),
                    "fused_mode": combo.get_tune(combo.TUNE_FUSED_MODE),
                    "tile_cols": combo.get_tune(combo.TUNE_TILE_COLS),
                    "xcd_swizzle": combo.get_tune(combo.TUNE_XCD_SWIZZLE)},
-        "effective_hbm_gbs": alg_bytes / (wall / args.steps) / 1e9,
-        "effective_hbm_pct_of_peak": 100.0 * alg_bytes / (wall / args.steps) / 1e9 / HBM_PEAK_GBS,
+        # (R+1) reads + 1 write per element over the step time: R of the reads are LDS reads, so
+        # this rate may exceed the HBM peak; it is not HBM utilisation (that is roofline.frac)
+        "effective_gbs": head["algorithmic_bytes_per_launch"] / (head["ms_per_step"] * 1e-3) / 1e9,
+        "effective_pct_of_hbm_peak": 100.0 * head["algorithmic_bytes_per_launch"] /
+        (head["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "roofline": {
             "bound": "hbm",
-            "kernel": kernel_name,
-            "achieved": achieved,
+            "kernel": head["kernel"],
+            "achieved": head["hbm_gbs"],
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBS,
-            "traffic": recorded_traffic(wl.name, args.layout),
-            "algorithmic_bytes_per_launch": alg_bytes,
-            "compulsory_bytes_per_launch": 8 * wl.N * wl.P + (4 * wl.N * wl.P if wl.fused else 0),
-            "kernel_ms_avg": kern_avg_ms,
-            "kernel_ms_median": kern_ms[len(kern_ms) // 2],
-            "kernel_ms_min": kern_ms[0],
+            "frac": head["hbm_frac"],
+            "bytes_per_launch": head["traffic"] or head["hbm_bytes_per_launch"],
+            "bytes_source": head["traffic_source"] or
+            "compulsory HBM bytes: every element read once and written once (8*N*P, +4*N*P gradient)",
+            "traffic": head["traffic"],
+            "traffic_source": head["traffic_source"],
+            "compulsory_bytes_per_launch": head["hbm_bytes_per_launch"],
+            "algorithmic_bytes_per_launch": head["algorithmic_bytes_per_launch"],
+            "effective_gbs": head["effective_gbs"],
+            "kernel_ms_avg": head["kernel_ms_avg"],
+            "kernel_ms_median": head["kernel_ms_median"],
+            "kernel_ms_min": head["kernel_ms_min"],
         },
     }
-    if other is not None:
-        out["other_layout"] = other
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, X0_host, args.cpu_budget)
-        out["cpu_baseline"]["host_cores_visible"] = os.cpu_count()
+    if "parity" in head:
+        out["parity"] = head["parity"]
+    if per_config:
+        out["per_config"] = per_config
+    if "cpu_baseline" in head:
+        out["cpu_baseline"] = head["cpu_baseline"]
     print(json.dumps(out), flush=True)
 
 

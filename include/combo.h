@@ -336,6 +336,41 @@ int combo_aggregation_divergence_noalloc(double* d_dist2, const float* d_x, int6
                                          int64_t P, void* stream);
 
 /*
+ * Bandwidth probes: gather-free passes with the memory access patterns of the aggregation
+ * kernels, to measure what the device sustains for each pattern (the practical ceiling a
+ * round is compared with).  They compute nothing of the method.  d_dst and d_src are
+ * float32 [N][ld] buffers (16-byte aligned, ld % 4 == 0, not overlapping); only whole
+ * 128-bit words, strips and tiles are touched, so a ragged remainder is left alone.
+ *   COMBO_PROBE_COPY        flat copy of the N*ld floats, 128-bit streaming loads and stores;
+ *                           param = words in flight per thread (1, 2, 4, 8); cols = 0: the
+ *                           words of a thread are 4 KiB apart, cols = 1: the words of one
+ *                           wavefront are consecutive KiB (also for the next two)
+ *   COMBO_PROBE_READ        the same loads folded to one float per workgroup, written to
+ *                           d_dst[workgroup] (d_dst needs N*ld / (1024*param) + 1 floats)
+ *   COMBO_PROBE_WRITE       the same stores of a constant; d_src may be NULL
+ *   COMBO_PROBE_ROW_CHUNKS  per workgroup N row chunks of `cols` columns, rows ld apart: the
+ *                           slab kernel's footprint on a row-major arena (no LDS, no gather)
+ *   COMBO_PROBE_TILES       per workgroup one contiguous N x cols tile: the footprint on a
+ *                           tiled arena; the first (P / cols)*N*cols floats are copied
+ *   COMBO_PROBE_MULTI_READ  d_dst[w][e] = sum of `param` rows w, w+1, ... (wrapping) of
+ *                           d_src, one workgroup per (1024 columns, row), rows in
+ *                           worker-major order: param read streams and one write stream with
+ *                           no reuse out of LDS
+ * Errors: COMBO_EINVAL for an unknown kind, bad sizes or pointers, or a cols/param the
+ * probe does not cover; COMBO_EALIAS for overlapping buffers.
+ */
+enum {
+    COMBO_PROBE_COPY = 0,
+    COMBO_PROBE_READ = 1,
+    COMBO_PROBE_WRITE = 2,
+    COMBO_PROBE_ROW_CHUNKS = 3,
+    COMBO_PROBE_TILES = 4,
+    COMBO_PROBE_MULTI_READ = 5
+};
+int combo_bandwidth_probe(int kind, float* d_dst, const float* d_src, int32_t N, int64_t ld, int64_t P,
+                          int32_t cols, int32_t param, void* stream);
+
+/*
  * Performance knobs (process-global, host side only; results never depend on them).
  *   COMBO_TUNE_KERNEL      0: automatic (LDS-slab kernel when the buffers are 16-byte
  *                          aligned, ld % 4 == 0 and N rows of a 64-column strip fit in
@@ -346,6 +381,11 @@ int combo_aggregation_divergence_noalloc(double* d_dist2, const float* d_x, int6
  *   COMBO_TUNE_SLAB_ORDER  slab kernel: 0: workgroup i works on strip i (consecutive strips go
  *                          round-robin to the 8 XCDs); 1: every XCD works through its own
  *                          contiguous eighth of the strips
+ *   COMBO_TUNE_SLAB_THREADS slab kernel: workgroup size; 0: automatic (256 threads for slabs of up
+ *                          to 12 KiB, else 512), or 256, 512
+ *   COMBO_TUNE_SLAB_LDS_FLOOR slab kernel: least LDS bytes a launch asks for (0..65536); above
+ *                          what the kernel uses it only lowers the number of workgroups
+ *                          resident per compute unit
  *   COMBO_TUNE_TILE_COLS   row-tile kernel: columns of one worker handled by one
  *                          workgroup: 0 = automatic (2048, or 1024 for more than 384
  *                          workers), or 1024, 2048, 4096
@@ -362,7 +402,9 @@ enum {
     COMBO_TUNE_FUSED_MODE = 2,
     COMBO_TUNE_KERNEL = 3,
     COMBO_TUNE_SLAB_COLS = 4,
-    COMBO_TUNE_SLAB_ORDER = 5
+    COMBO_TUNE_SLAB_ORDER = 5,
+    COMBO_TUNE_SLAB_THREADS = 6,
+    COMBO_TUNE_SLAB_LDS_FLOOR = 7
 };
 int combo_tune(int key, int value);
 /* Which kernel the row-major aggregation entry points use for N workers and R replicas

@@ -19,13 +19,18 @@ _f32p = ctypes.POINTER(ctypes.c_float)
 _f64p = ctypes.POINTER(ctypes.c_double)
 
 
-def lib():
+def lib(path=None):
+    """The oracle's shared object, loaded once.  `path` (first call only) names another
+    build of it: the mutation tests pass a deliberately wrong copy to show that the pins
+    catch it.  Nothing but an explicit argument can replace the oracle."""
     global _LIB
+    if _LIB is not None and path is not None:
+        raise RuntimeError("the oracle is already loaded; a different build must be named on the first call")
     if _LIB is None:
-        # COMBO_REF_LIB: load another build of the oracle (used by the mutation tests)
-        path = os.environ.get("COMBO_REF_LIB") or _build.LIB
-        if path == _build.LIB and not os.path.exists(path):
-            _build.build()
+        if path is None:
+            path = _build.LIB
+            if not os.path.exists(path):
+                _build.build()
         L = ctypes.CDLL(path)
         L.combo_ref_segment_bounds.argtypes = [ctypes.c_int64, ctypes.c_int32, _i64p, _i64p]
         L.combo_ref_segment_bounds.restype = ctypes.c_int

@@ -13,8 +13,10 @@ TUNE_FUSED_MODE = 2
 TUNE_KERNEL = 3
 TUNE_SLAB_COLS = 4
 TUNE_SLAB_ORDER = 5
+TUNE_SLAB_THREADS = 6
+TUNE_SLAB_LDS_FLOOR = 7
 
-EXPORTS = ("combo_round_relayout", "combo_aggregation_divergence_noalloc", "combo_round_hashed", "combo_round_kernel_kind", "combo_aggregation_divergence_tiled", "combo_tiled_cols", "combo_tiled_elems", "combo_pack_tiled", "combo_unpack_tiled",
+EXPORTS = ("combo_bandwidth_probe", "combo_round_relayout", "combo_aggregation_divergence_noalloc", "combo_round_hashed", "combo_round_kernel_kind", "combo_aggregation_divergence_tiled", "combo_tiled_cols", "combo_tiled_elems", "combo_pack_tiled", "combo_unpack_tiled",
            "combo_segment_gossip_round_tiled", "combo_local_sgd_steps_then_gossip_tiled",
            "combo_local_sgd_steps_then_gossip", "combo_aggregation_divergence", "combo_aggregation_divergence_workspace",
            "combo_make_peer_table_dynamic", "combo_segment_gossip_round_dynamic",
@@ -87,6 +89,8 @@ def lib():
         L.combo_round_relayout.argtypes = [vp, i64, i32, vp, i64, i32, vp, i32, f32, vp, vp, vp, i32, i64,
                                            i32, i32, vp]
         L.combo_round_relayout.restype = ctypes.c_int
+        L.combo_bandwidth_probe.argtypes = [ctypes.c_int, vp, vp, i32, i64, i64, i32, i32, vp]
+        L.combo_bandwidth_probe.restype = ctypes.c_int
         L.combo_round_hashed.argtypes = [vp, vp, vp, i32, f32, i64, i32, vp, i32, i64, i32, i32, u64, u64, vp]
         L.combo_round_hashed.restype = ctypes.c_int
         L.combo_round_kernel_kind.argtypes = [i32, i32]
@@ -462,6 +466,24 @@ def round_relayout(dst, dst_tile_cols, src, src_tile_cols, peers, N, P, S, R, *,
                                     N, P, S, R, _stream_ptr(stream))
     if rc:
         raise ComboError(rc, "combo_round_relayout")
+    return dst
+
+
+PROBE_COPY, PROBE_READ, PROBE_WRITE, PROBE_ROW_CHUNKS, PROBE_TILES, PROBE_MULTI_READ = range(6)
+
+
+def bandwidth_probe(kind, dst, src, P, cols=0, param=4, stream=None):
+    """combo_bandwidth_probe on (N, ld) float32 device matrices (src may be None for the
+    write-only probe)."""
+    N = dst.shape[0]
+    ld = _matrix(dst, "dst")
+    if src is not None and (src.shape[0] != N or _matrix(src, "src") != ld):
+        raise ValueError("src must have dst's row count and pitch")
+    rc = lib().combo_bandwidth_probe(int(kind), _dev_ptr(dst, torch.float32, "dst"),
+                                     _dev_ptr(src, torch.float32, "src", optional=True), N, ld, P,
+                                     int(cols), int(param), _stream_ptr(stream))
+    if rc:
+        raise ComboError(rc, "combo_bandwidth_probe")
     return dst
 
 

@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcombo.so")
 SOURCES = ["combo_api.hip", "gossip_round.hip", "gossip_slab.hip", "gossip_slab_hashed.hip", "gossip_slab_dynamic.hip", "peer_table.hip",
-           "divergence.hip", "layout.hip"]
+           "divergence.hip", "layout.hip", "probe.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -131,6 +131,9 @@ int enqueue_round(float* dst, const float* src, const float* grad, float lr, int
         if (strips > kMaxStrips) return COMBO_ERANGE;
         a.nstrips = (uint32_t)strips;
         if (g_slab_order.load() == 1) a.strips_per_xcd = (a.nstrips + combo::kXcds - 1) / combo::kXcds;
+        // a grid dimension holds fewer than 2^32 work-items
+        const uint64_t groups = a.strips_per_xcd != 0 ? (uint64_t)combo::kXcds * a.strips_per_xcd : strips;
+        if (groups * (uint64_t)combo::slab_threads(N, plan.cols) > 0xFFFFFFFFull) return COMBO_ERANGE;
     }
     a.hash_sr = hash_sr;
     if (hashed)
@@ -541,6 +544,21 @@ int combo_aggregation_divergence_noalloc(double* d_dist2, const float* d_x, int6
                               (hipStream_t)stream);
 }
 
+int combo_bandwidth_probe(int kind, float* d_dst, const float* d_src, int32_t N, int64_t ld, int64_t P,
+                          int32_t cols, int32_t param, void* stream) {
+    if (kind < COMBO_PROBE_COPY || kind > COMBO_PROBE_MULTI_READ) return COMBO_EINVAL;
+    if (N < 1 || P < 1 || ld < P || d_dst == nullptr) return COMBO_EINVAL;
+    if (kind != COMBO_PROBE_WRITE && d_src == nullptr) return COMBO_EINVAL;
+    if (!aligned16(d_dst) || !aligned16(d_src) || ld % 4 != 0) return COMBO_EINVAL;
+    if ((uint64_t)ld > (UINT64_MAX / 4) / (uint64_t)N) return COMBO_ERANGE;
+    const uint64_t bytes = (uint64_t)N * (uint64_t)ld * 4;
+    if (d_src != nullptr && overlaps(d_dst, bytes, d_src, bytes)) return COMBO_EALIAS;
+    const hipError_t e = combo::launch_bandwidth_probe(kind, d_dst, d_src, N, ld, P, cols, param,
+                                                       (hipStream_t)stream);
+    if (e == hipErrorInvalidValue) return COMBO_EINVAL;
+    return e == hipSuccess ? COMBO_OK : COMBO_EHIP;
+}
+
 int combo_round_kernel_kind(int32_t N, int32_t R) {
     if (N < 1 || R < 0) return COMBO_EINVAL;
     if (g_kernel.load() == 1) return 0;
@@ -574,6 +592,14 @@ int combo_tune(int key, int value) {
             if (value != 0 && value != 1) return COMBO_EINVAL;
             g_slab_order.store(value);
             return COMBO_OK;
+        case COMBO_TUNE_SLAB_THREADS:
+            if (value != 0 && value != 256 && value != 512) return COMBO_EINVAL;
+            combo::set_slab_threads(value);
+            return COMBO_OK;
+        case COMBO_TUNE_SLAB_LDS_FLOOR:
+            if (value < 0 || value > 64 * 1024) return COMBO_EINVAL;
+            combo::set_slab_lds_floor(value);
+            return COMBO_OK;
         default:
             return COMBO_EINVAL;
     }
@@ -587,6 +613,8 @@ int combo_get_tune(int key) {
         case COMBO_TUNE_KERNEL: return g_kernel.load();
         case COMBO_TUNE_SLAB_COLS: return g_slab_cols.load();
         case COMBO_TUNE_SLAB_ORDER: return g_slab_order.load();
+        case COMBO_TUNE_SLAB_THREADS: return combo::get_slab_threads();
+        case COMBO_TUNE_SLAB_LDS_FLOOR: return combo::get_slab_lds_floor();
         default: return COMBO_EINVAL;
     }
 }

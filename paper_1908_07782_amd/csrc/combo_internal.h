@@ -77,6 +77,10 @@ hipError_t launch_pack_tiled(float* tiled, const float* rows, int64_t ld, int32_
 hipError_t launch_unpack_tiled(float* rows, int64_t ld, const float* tiled, int32_t N, int64_t P,
                                int tile_cols, hipStream_t st);
 
+// gather-free passes with the kernels' memory access patterns (probe.hip)
+hipError_t launch_bandwidth_probe(int kind, float* dst, const float* src, int32_t N, int64_t ld, int64_t P,
+                                  int cols, int param, hipStream_t st);
+
 // Slab kernel: one workgroup stages all N rows of a strip of `strip_cols` columns in
 // LDS.  slab_strip_cols() picks the strip width for N workers (0: does not fit in LDS).
 int slab_strip_cols(int32_t N, int32_t R, int requested, bool hashed = false);
@@ -88,7 +92,12 @@ hipError_t launch_round_slab_dynamic(const RoundArgs& a, int strip_cols, uint32_
                                      hipStream_t st);
 size_t slab_lds_bytes(int32_t N, int32_t R, int strip_cols, bool hashed);
 uint32_t slab_grid(const RoundArgs& a, int strip_cols);
+size_t slab_lds_request(int32_t N, int32_t R, int strip_cols, bool hashed);
+void set_slab_lds_floor(int bytes);   // least LDS a slab launch asks for (limits resident workgroups)
+int get_slab_lds_floor();
 int slab_threads(int32_t N, int strip_cols);
+void set_slab_threads(int threads);   // 0: automatic, else 256 or 512
+int get_slab_threads();
 
 // number of workgroups launch_round would use, or 0 if that exceeds the grid limit
 uint64_t round_grid_size(int32_t N, int64_t P, int tile_cols, bool swizzle);

@@ -1,5 +1,7 @@
 // Table-driven instantiations of the LDS-slab aggregation kernel (gossip_slab_kernel.h)
 // and the host-side choices around it: strip width, workgroup size, LDS budget.
+#include <atomic>
+
 #include "gossip_slab_kernel.h"
 
 namespace combo {
@@ -10,8 +12,34 @@ size_t slab_lds_bytes(int32_t N, int32_t R, int W, bool hashed) {
     return (size_t)N * (size_t)W * 4 + (hashed ? 2 : 1) * (size_t)N * (size_t)R * 4 + 3 * (size_t)N * 4;
 }
 
-// 256 threads for slabs of up to 768 128-bit words (12 KiB), 512 beyond
-int slab_threads(int32_t N, int W) { return (int64_t)N * (W / 4) <= 768 ? 256 : 512; }
+// 256 threads for slabs of up to 768 128-bit words (12 KiB), 512 beyond; or what the knob says
+std::atomic<int> g_slab_threads{0};
+void set_slab_threads(int threads) { g_slab_threads.store(threads); }
+int get_slab_threads() { return g_slab_threads.load(); }
+int slab_threads(int32_t N, int W) {
+    const int forced = g_slab_threads.load();
+    if (forced != 0) return forced;
+    return (int64_t)N * (W / 4) <= 768 ? 256 : 512;
+}
+
+// LDS to ask for at launch: at least what the kernel uses.  Asking for more lowers the number
+// of workgroups resident per compute unit (160 KiB of LDS each).  Measured on MI355X with
+// 256-thread workgroups and 8 KiB slabs: six resident workgroups (23..26 KiB each) stream
+// 1-2.5 % faster than the eight that the wavefront limit allows (c5: 6.79 vs 6.93 ms; fewer
+// requests competing in the memory system), five or fewer are slower (c5: 7.72 ms).  That holds
+// while the aggregation phase is short: from R = 8 on the two extra workgroups are worth more
+// for hiding it (30 workers, R = 8: 1.03 vs 1.05 ms, R = 16: 1.17 vs 1.22 ms), so the rule
+// applies up to R = 4.  512-thread workgroups are four per compute unit anyway.  The knob:
+// 0 = this rule, else the floor in bytes.
+std::atomic<int> g_slab_lds_floor{0};
+void set_slab_lds_floor(int bytes) { g_slab_lds_floor.store(bytes); }
+int get_slab_lds_floor() { return g_slab_lds_floor.load(); }
+size_t slab_lds_request(int32_t N, int32_t R, int W, bool hashed) {
+    const size_t used = slab_lds_bytes(N, R, W, hashed);
+    size_t floor_bytes = (size_t)g_slab_lds_floor.load();
+    if (floor_bytes == 0 && slab_threads(N, W) == 256 && R <= 4) floor_bytes = 24 * 1024;
+    return used > floor_bytes ? used : floor_bytes;
+}
 
 namespace {
 
@@ -64,13 +92,16 @@ int slab_strip_cols(int32_t N, int32_t R, int requested, bool hashed) {
 uint32_t slab_grid(const RoundArgs& a, int W) {
     const uint64_t strips = ((uint64_t)a.P + (uint64_t)W - 1) / (uint64_t)W;
     if (strips > 0x7FFFFFF0ull || strips != a.nstrips) return 0;
-    return a.strips_per_xcd != 0 ? (uint32_t)kXcds * a.strips_per_xcd : a.nstrips;
+    const uint32_t grid = a.strips_per_xcd != 0 ? (uint32_t)kXcds * a.strips_per_xcd : a.nstrips;
+    // a grid dimension holds fewer than 2^32 work-items
+    if ((uint64_t)grid * (uint64_t)slab_threads(a.N, W) > 0xFFFFFFFFull) return 0;
+    return grid;
 }
 
 hipError_t launch_round_slab(const RoundArgs& a, int W, hipStream_t st) {
     const uint32_t grid = slab_grid(a, W);
     if (grid == 0) return hipErrorInvalidValue;
-    const size_t lds = slab_lds_bytes(a.N, a.R, W, false);
+    const size_t lds = slab_lds_request(a.N, a.R, W, false);
     if (a.status != nullptr) return launch_round_slab_dynamic(a, W, grid, lds, st);
     switch (a.R) {
         case 0: return launch_rt<0>(a, W, grid, lds, st);

@@ -46,13 +46,24 @@ __device__ __forceinline__ v4f scale4(float s, v4f a) {
     return y;
 }
 
-// Quotients by a shared denominator.  Given r = fl(1/d), a / d is obtained, correctly
-// rounded, with one multiply and two fused multiply-adds instead of a division: the
-// product q0 = fl(a*r) is within one ulp of the quotient, the residual a - q0*d is exact
-// in one fma, and fl(q0 + residual*r) is the correctly rounded quotient (Markstein's
-// division theorem) as long as nothing under- or overflows on the way.  That holds for d
-// and |a| in [2^-60, 2^60]; a zero numerator gives a zero of the numerator's sign.
-// Everything else takes the division instruction sequence.
+// Quotients by a shared denominator.  Given r = RN(1/d) (the correctly rounded reciprocal),
+// a / d is obtained, correctly rounded, with one multiply and four fused multiply-adds
+// instead of a division sequence per element:
+//     q0 = RN(a*r)                        within 2 ulp of a/d (r and the product each
+//                                         contribute a relative error of up to 2^-24); NOT
+//                                         necessarily faithful, so its residual a - q0*d
+//                                         need not be exact
+//     q1 = RN(q0 + RN(a - q0*d)*r)        one correction: q1 = RN(a/d + e) with |e| far
+//                                         below an ulp, hence faithful (one of the two
+//                                         floats around a/d), though e could still tip a
+//                                         quotient that lies very close to a midpoint
+//     q2 = RN(q1 + (a - q1*d)*r)          the residual of a faithful quotient is exact in
+//                                         one fma, and with r = RN(1/d) this last step
+//                                         returns RN(a/d) (Markstein's theorem on the
+//                                         final correction of a division)
+// provided nothing under- or overflows on the way, which holds for d and |a| in
+// [2^-60, 2^60] (the residuals are multiples of 2^-46*|a|).  A zero numerator gives a zero
+// of the numerator's sign.  Everything else takes the division instruction sequence.
 constexpr uint32_t kDivLoBits = 0x21800000u;   // 2^-60
 constexpr uint32_t kDivHiBits = 0x5d800000u;   // 2^60
 
@@ -64,7 +75,8 @@ __device__ __forceinline__ float shared_reciprocal(float d) {
 __device__ __forceinline__ float quotient_by_reciprocal(float a, float d, float r) {
     const float q0 = __fmul_rn(a, r);
     const float q1 = __fmaf_rn(__fmaf_rn(-q0, d, a), r, q0);
-    return __builtin_copysignf(q1, a);           // only matters for a == -0
+    const float q2 = __fmaf_rn(__fmaf_rn(-q1, d, a), r, q1);
+    return __builtin_copysignf(q2, a);           // only matters for a == -0
 }
 
 // the four quotients of one 128-bit word by the same denominator; r = shared_reciprocal(d)

@@ -59,8 +59,20 @@ def test_a_planted_mistake_is_caught(tmp_path, name, old, new):
     lib = tmp_path / "libcombo_ref_mutant.so"
     subprocess.run(["g++", "-std=c++17", "-O1", "-ffp-contract=off", "-fPIC", "-shared", "-o", str(lib),
                     str(mutant_src)], check=True)
-    env = dict(os.environ, COMBO_REF_LIB=str(lib))
-    out = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider"] + PIN_FILES,
-                         cwd=ROOT, env=env, capture_output=True, text=True, timeout=300)
+    out = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
+                          "--oracle-lib", str(lib)] + PIN_FILES,
+                         cwd=ROOT, capture_output=True, text=True, timeout=300)
     # a failed pin or a crash (some mutants write out of bounds) both count as caught
     assert out.returncode != 0, f"mutant {name} passed every pin:\n{out.stdout[-2000:]}"
+
+
+def test_the_same_route_passes_with_an_unmodified_copy(tmp_path):
+    """The control: a copy of the oracle as it stands, built and loaded the same way, passes
+    every pin, so a non-zero exit above means a pin failed and not that the run went wrong."""
+    lib = tmp_path / "libcombo_ref_copy.so"
+    subprocess.run(["g++", "-std=c++17", "-O1", "-ffp-contract=off", "-fPIC", "-shared", "-o", str(lib), SRC],
+                   check=True)
+    out = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
+                          "--oracle-lib", str(lib)] + PIN_FILES,
+                         cwd=ROOT, capture_output=True, text=True, timeout=600)
+    assert out.returncode == 0, out.stdout[-2000:] + out.stderr[-1000:]
