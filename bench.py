@@ -79,16 +79,26 @@ def sweep_paper(combo, P, layout="rows"):
     d2 = torch.empty(N, dtype=torch.float64, device="cuda")
     tiled = layout == "tiled"
     if tiled:
-        Wt = combo.tiled_cols(N, 2)
-        arena = torch.zeros((2, combo.tiled_elems(N, P, Wt)), dtype=torch.float32, device="cuda")
-        combo.pack_tiled(arena[0], rows, N, P, Wt)
-        del rows
+        # the tile width follows the replica count (combo_tiled_cols): the arena is packed anew
+        # when it changes
+        state = {"Wt": 0, "arena": None}
+
+        def arena_for(R):
+            Wt = combo.tiled_cols(N, R)
+            if Wt != state["Wt"]:
+                state["arena"] = None
+                state["arena"] = torch.zeros((2, combo.tiled_elems(N, P, Wt)), dtype=torch.float32, device="cuda")
+                combo.pack_tiled(state["arena"][0], rows, N, P, Wt)
+                state["Wt"] = Wt
+            return state["arena"], Wt
 
         def one_round(peers, S, R):
+            arena, Wt = arena_for(R)
             combo.segment_gossip_round_tiled(arena[1], arena[0], Wt, peers, N, P, S, R, stream=stream)
 
-        def rho_of(x):
-            combo.aggregation_divergence_tiled(d2, x, Wt, N, P, ws, stream=stream)
+        def rho_of(which, R):
+            arena, Wt = arena_for(R)
+            combo.aggregation_divergence_tiled(d2, arena[which], Wt, N, P, ws, stream=stream)
             return float(d2.max().sqrt())
     else:
         arena = torch.zeros((2, N, ld), dtype=torch.float32, device="cuda")
@@ -98,17 +108,18 @@ def sweep_paper(combo, P, layout="rows"):
         def one_round(peers, S, R):
             combo.segment_gossip_round(arena[1], arena[0], peers, P, S, R, stream=stream)
 
-        def rho_of(x):
-            combo.aggregation_divergence(d2, x, P, ws, stream=stream)
+        def rho_of(which, R):
+            combo.aggregation_divergence(d2, arena[which], P, ws, stream=stream)
             return float(d2.max().sqrt())
-    rho0 = rho_of(arena[0])
+    rho0 = rho_of(0, 2)
     for which, S, R in points:
         peers = torch.empty(N * S * R, dtype=torch.int32, device="cuda")
         combo.make_peer_table(peers, N, S, R, 0, 0)
         ms = time_kernel(lambda: one_round(peers, S, R), stream)
         # aggregation divergence (Sec. 4.3, Def. 2) after this one round from independent models
-        rho = rho_of(arena[1])
-        print(json.dumps({"sweep": which, "layout": layout, "N": N, "P": P, "S": S, "R": R, "kernel_ms": ms,
+        rho = rho_of(1, R)
+        print(json.dumps({"sweep": which, "layout": layout, "N": N, "P": P, "S": S, "R": R,
+                          "tiled_cols": combo.tiled_cols(N, R) if tiled else 0, "kernel_ms": ms,
                           "rounds_per_s": 1e3 / ms,
                           "effective_GBs": 4 * (R + 2) * N * P / ms / 1e6,
                           "compulsory_GBs": 8 * N * P / ms / 1e6,

@@ -84,6 +84,7 @@ hipError_t launch_bandwidth_probe(int kind, float* dst, const float* src, int32_
 // Slab kernel: one workgroup stages all N rows of a strip of `strip_cols` columns in
 // LDS.  slab_strip_cols() picks the strip width for N workers (0: does not fit in LDS).
 int slab_strip_cols(int32_t N, int32_t R, int requested, bool hashed = false);
+size_t slab_budget_bytes(int32_t R, bool tiled);   // slab size the strip and tile widths aim for
 hipError_t launch_round_slab(const RoundArgs& a, int strip_cols, hipStream_t st);
 // the same kernel drawing its peers in-kernel from a.hash_sr (R <= 8, no table)
 hipError_t launch_round_slab_hashed(const RoundArgs& a, int strip_cols, hipStream_t st);

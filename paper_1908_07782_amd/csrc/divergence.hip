@@ -82,35 +82,39 @@ __global__ __launch_bounds__(kDivThreads) void divergence_partial_kernel(const D
     const double inv_den = 1.0 / den;                 // one division per thread, not four per strip
 
     double wt[kDivSlots];                             // dataset size of each slot's row
+    // Where slot k's 128-bit word lives relative to the strip's base: the part of the address
+    // that does not change from strip to strip (row-major: row*ld + c; tiled: a strip spans
+    // W/Wt whole tiles, the word is in tile c/Wt of them).  Per strip only the base is added.
+    size_t slot_off[kDivSlots];
 #pragma unroll
     for (int k = 0; k < kDivSlots; ++k) {
         const int row = k * groups + my_row0;
         wt[k] = (WEIGHTED && row < N) ? (double)lds_d[row] : 1.0;
+        const size_t c = (size_t)my_c4 * 4;
+        if (a.tile_shift == 0)
+            slot_off[k] = (size_t)row * (size_t)a.ld + c;
+        else
+            slot_off[k] = (((c >> a.tile_shift) * (size_t)N + (size_t)row) << a.tile_shift) +
+                          (c & (((size_t)1 << a.tile_shift) - 1));
     }
     double acc[kDivSlots];
 #pragma unroll
     for (int k = 0; k < kDivSlots; ++k) acc[k] = 0.0;
+    const size_t strip_elems = a.tile_shift == 0 ? (size_t)W : (size_t)N * (size_t)W;
 
     int buf = 0;
     for (uint32_t strip = blockIdx.x; strip < a.nstrips; strip += gridDim.x) {
         const int64_t col0 = (int64_t)strip * W;
         const int width = (int)(col0 + W <= a.P ? W : a.P - col0);
         const bool fast = a.vec && width == W;
+        const float* base = a.x + (size_t)strip * strip_elems;
         v4f v[kDivSlots];
 #pragma unroll
         for (int k = 0; k < kDivSlots; ++k) {
             const int row = k * groups + my_row0;
             if (k * kDivThreads < total4 && row < N) {
                 const int c = my_c4 * 4;
-                const float* p;
-                if (a.tile_shift == 0) {
-                    p = a.x + (size_t)row * (size_t)a.ld + (size_t)col0 + (size_t)c;
-                } else {                              // the four columns lie in one tile
-                    const size_t col = (size_t)col0 + (size_t)c;
-                    const size_t tile = col >> a.tile_shift;
-                    const size_t in_tile = col & (((size_t)1 << a.tile_shift) - 1);
-                    p = a.x + ((tile * (size_t)N + (size_t)row) << a.tile_shift) + in_tile;
-                }
+                const float* p = base + slot_off[k];
                 if (fast) {
                     v[k] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
                 } else {                              // ragged end or unaligned: zero beyond the row

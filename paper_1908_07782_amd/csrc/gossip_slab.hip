@@ -69,11 +69,21 @@ hipError_t launch_rt(const RoundArgs& a, int W, uint32_t grid, size_t lds, hipSt
 
 }  // namespace
 
-// Strip width: the widest power of two in [64, 1024] columns whose slab is at most
-// 16 KiB (two 128-bit words per thread, four workgroups per compute unit); for many
-// workers 64 columns as long as slab, peer list and weights fit in 64 KiB of LDS.
-// `requested` != 0 forces a width if it fits (tiled arenas: their tile width, down to 8
-// columns).
+// Slab budget.  Up to 8 replicas the aggregation phase is short and small slabs stream best.
+// Beyond, a workgroup spends longer adding (R+1 LDS reads per output word), and what hides
+// that is more data in flight per compute unit: 32 KiB slabs with 512 threads (measured, 30
+// workers of 25.6 M parameters, R = 16: 1.05 ms against 1.16 ms with 8 KiB slabs and 1.02 ms
+// at R = 4; R = 29: 1.38 against 1.59 ms).
+size_t slab_budget_bytes(int32_t R, bool tiled) {
+    if (R > 8) return 32 * 1024;
+    return tiled ? 8 * 1024 : 16 * 1024;
+}
+
+// Strip width: the widest power of two in [64, 1024] columns whose slab is within the budget
+// (row-major arenas: 16 KiB, two 128-bit words per thread of a 512-thread workgroup; 32 KiB
+// for more than 8 replicas); for many workers 64 columns as long as slab, peer list and
+// weights fit in 64 KiB of LDS.  `requested` != 0 forces a width if it fits (tiled arenas:
+// their tile width, down to 8 columns).
 int slab_strip_cols(int32_t N, int32_t R, int requested, bool hashed) {
     const size_t kLimit = 64 * 1024;
     if (requested) {
@@ -82,8 +92,9 @@ int slab_strip_cols(int32_t N, int32_t R, int requested, bool hashed) {
             slab_lds_bytes(N, R, requested, hashed) <= kLimit)
             return requested;
     }
+    const size_t budget = slab_budget_bytes(R, false);
     for (int W = 1024; W >= 64; W >>= 1)
-        if ((size_t)N * (size_t)W * 4 <= 16 * 1024 && slab_lds_bytes(N, R, W, hashed) <= kLimit) return W;
+        if ((size_t)N * (size_t)W * 4 <= budget && slab_lds_bytes(N, R, W, hashed) <= kLimit) return W;
     return slab_lds_bytes(N, R, 64, hashed) <= kLimit ? 64 : 0;
 }
 
