@@ -182,11 +182,12 @@ def extras(combo, wl):
     emit("round with R=0, tiled (copy through the slab kernel)", time_kernel(
         lambda: combo.segment_gossip_round_tiled(t0[1], t0[0], wt0, None, N, P, S, 0, stream=stream),
         stream), 8 * N * P, note="bytes = read + write", tiled_cols=wt0)
-    # the round itself, row-major, with the two strip orders (A/B in one process), and the
-    # rounds that change layout on the way (no pack / unpack pass)
+    # the round itself with the two strip orders (1: workgroup i takes strip i, 2: a contiguous
+    # eighth of the strips per XCD; A/B in one process), and the rounds that change layout on
+    # the way (no pack / unpack pass)
     combo.make_peer_table(peers, N, S, R, 0, 1)
     for rep in range(2):
-        for order in (0, 1):
+        for order in (1, 2):
             combo.tune(combo.TUNE_SLAB_ORDER, order)
             emit(f"combo_segment_gossip_round, row-major, strip order {order} (pass {rep})", time_kernel(
                 lambda: combo.segment_gossip_round(arena[1], arena[0], peers, P, S, R, stream=stream), stream),

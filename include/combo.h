@@ -380,9 +380,11 @@ int combo_bandwidth_probe(int kind, float* d_dst, const float* d_src, int32_t N,
  *                          row-tile kernel; 2: same as 0
  *   COMBO_TUNE_SLAB_COLS   strip width of the slab kernel: 0 = automatic, or a power of
  *                          two in [64, 1024] (ignored if that slab does not fit in LDS)
- *   COMBO_TUNE_SLAB_ORDER  slab kernel: 0: workgroup i works on strip i (consecutive strips go
- *                          round-robin to the 8 XCDs); 1: every XCD works through its own
- *                          contiguous eighth of the strips
+ *   COMBO_TUNE_SLAB_ORDER  slab kernel: 1: workgroup i works on strip i (consecutive strips go
+ *                          round-robin to the 8 XCDs); 2: every XCD works through its own
+ *                          contiguous eighth of the strips; 0: automatic (the eighths for
+ *                          tiled arenas of at least 8 GiB per matrix, where they measure
+ *                          2-8 % faster; strip i everywhere else)
  *   COMBO_TUNE_SLAB_THREADS slab kernel: workgroup size; 0: automatic (256 threads for slabs of up
  *                          to 12 KiB, else 512), or 256, 512
  *   COMBO_TUNE_SLAB_LDS_FLOOR slab kernel: least LDS bytes a launch asks for (0..65536); above

@@ -14,7 +14,7 @@ std::atomic<int> g_swizzle{1};
 std::atomic<int> g_fused_mode{0};
 std::atomic<int> g_kernel{0};
 std::atomic<int> g_slab_cols{0};
-std::atomic<int> g_slab_order{0};             // 0: strip i to workgroup i; 1: contiguous strips per XCD
+std::atomic<int> g_slab_order{0};             // 0: by size and layout; 1: strip i to workgroup i; 2: contiguous strips per XCD
 
 enum PlanKind { kPlanTile = 0, kPlanSlab = 1 };
 struct Plan {
@@ -130,7 +130,17 @@ int enqueue_round(float* dst, const float* src, const float* grad, float lr, int
         const uint64_t strips = ((uint64_t)P + (uint64_t)plan.cols - 1) / (uint64_t)plan.cols;
         if (strips > kMaxStrips) return COMBO_ERANGE;
         a.nstrips = (uint32_t)strips;
-        if (g_slab_order.load() == 1) a.strips_per_xcd = (a.nstrips + combo::kXcds - 1) / combo::kXcds;
+        // Which strips a workgroup takes.  Workgroup ids go round-robin over the 8 XCDs, so with
+        // strip = id all XCDs move through the arena together; the alternative gives every XCD
+        // its own contiguous eighth.  Measured on MI355X: the eighths cost 2-10 % up to about
+        // 5 GiB per matrix and 10-15 % on row-major arenas at any size (the L2 -> fabric
+        // request stalls double to triple), but gain 2-8 % on tiled arenas from about 10 GiB
+        // per matrix on (16 x 335 M: 6.64 vs 6.79 ms).
+        const int order = g_slab_order.load();
+        const bool both_tiled = a.tile_shift != 0 && a.dst_tile_shift != 0;
+        const bool eighths = order == 2 || (order == 0 && both_tiled &&
+                                            (uint64_t)N * (uint64_t)P * sizeof(float) >= (8ull << 30));
+        if (eighths) a.strips_per_xcd = (a.nstrips + combo::kXcds - 1) / combo::kXcds;
         // a grid dimension holds fewer than 2^32 work-items
         const uint64_t groups = a.strips_per_xcd != 0 ? (uint64_t)combo::kXcds * a.strips_per_xcd : strips;
         if (groups * (uint64_t)combo::slab_threads(N, plan.cols) > 0xFFFFFFFFull) return COMBO_ERANGE;
@@ -591,7 +601,7 @@ int combo_tune(int key, int value) {
             g_slab_cols.store(value);
             return COMBO_OK;
         case COMBO_TUNE_SLAB_ORDER:
-            if (value != 0 && value != 1) return COMBO_EINVAL;
+            if (value < 0 || value > 2) return COMBO_EINVAL;
             g_slab_order.store(value);
             return COMBO_OK;
         case COMBO_TUNE_SLAB_THREADS:

@@ -281,7 +281,7 @@ def test_short_segments_table_free_round(combo, ref, N, P, S, R, weighted, layou
 def test_strip_order_does_not_change_results(combo, ref, N, P, S, R, layout):
     """Every XCD working through its own contiguous range of strips (strip counts that are and
     are not multiples of 8, fewer strips than XCDs) gives the same bits."""
-    combo.tune(combo.TUNE_SLAB_ORDER, 1)
+    combo.tune(combo.TUNE_SLAB_ORDER, 2)
     Xh = np.random.default_rng(P).normal(0, 0.05, (N, P)).astype(np.float32)
     Wt = combo.tiled_cols(N, R) if layout == "tiled" else 0
     src = Side(combo, N, P, Wt, Xh)
