@@ -150,6 +150,12 @@ def extras(combo, wl):
         emit(f"probe: flat copy, {flight} x 128-bit words in flight per thread", time_kernel(
             lambda: combo.bandwidth_probe(combo.PROBE_COPY, arena[1], arena[0], P, param=flight, stream=stream),
             stream), 2 * foot, note="bytes = read + write")
+    for flight in (1, 2):
+        # the same copy with the XCDs taking turns at runs of 128 KiB of consecutive blocks
+        run = 128 * 1024 // (4096 * flight)
+        emit(f"probe: flat copy, {flight} words in flight, XCD runs of {run} blocks (128 KiB)", time_kernel(
+            lambda: combo.bandwidth_probe(combo.PROBE_COPY, arena[1], arena[0], P, cols=run << 4, param=flight,
+                                          stream=stream), stream), 2 * foot, note="bytes = read + write")
     for flight in (4, 8):
         emit(f"probe: read only, {flight} words in flight", time_kernel(
             lambda: combo.bandwidth_probe(combo.PROBE_READ, arena[1], arena[0], P, param=flight, stream=stream),

@@ -344,9 +344,11 @@ int combo_aggregation_divergence_noalloc(double* d_dist2, const float* d_x, int6
  * float32 [N][ld] buffers (16-byte aligned, ld % 4 == 0, not overlapping); only whole
  * 128-bit words, strips and tiles are touched, so a ragged remainder is left alone.
  *   COMBO_PROBE_COPY        flat copy of the N*ld floats, 128-bit streaming loads and stores;
- *                           param = words in flight per thread (1, 2, 4, 8); cols = 0: the
- *                           words of a thread are 4 KiB apart, cols = 1: the words of one
- *                           wavefront are consecutive KiB (also for the next two)
+ *                           param = words in flight per thread (1, 2, 4, 8); cols bit 0 = 0:
+ *                           the words of a thread are 4 KiB apart, 1: the words of one
+ *                           wavefront are consecutive KiB; cols >> 4 = k != 0: the XCDs take
+ *                           turns at runs of k consecutive workgroup blocks, as the slab
+ *                           kernel's strip order does (also for the next two)
  *   COMBO_PROBE_READ        the same loads folded to one float per workgroup, written to
  *                           d_dst[workgroup] (d_dst needs N*ld / (1024*param) + 1 floats)
  *   COMBO_PROBE_WRITE       the same stores of a constant; d_src may be NULL
@@ -380,11 +382,12 @@ int combo_bandwidth_probe(int kind, float* d_dst, const float* d_src, int32_t N,
  *                          row-tile kernel; 2: same as 0
  *   COMBO_TUNE_SLAB_COLS   strip width of the slab kernel: 0 = automatic, or a power of
  *                          two in [64, 1024] (ignored if that slab does not fit in LDS)
- *   COMBO_TUNE_SLAB_ORDER  slab kernel: 1: workgroup i works on strip i (consecutive strips go
- *                          round-robin to the 8 XCDs); 2: every XCD works through its own
- *                          contiguous eighth of the strips; 0: automatic (the eighths for
- *                          tiled arenas of at least 8 GiB per matrix, where they measure
- *                          2-8 % faster; strip i everywhere else)
+ *   COMBO_TUNE_SLAB_ORDER  slab kernel, which strip a workgroup takes (workgroup ids go round-robin
+ *                          over the 8 XCDs): 1: workgroup i takes strip i; 2: every XCD works
+ *                          through its own contiguous eighth of the strips; k >= 3: the XCDs
+ *                          take turns at runs of k consecutive strips; 0: automatic (runs of
+ *                          16 for tiled arenas, where they measure 1.5-7 % faster; strip i
+ *                          for row-major ones)
  *   COMBO_TUNE_SLAB_THREADS slab kernel: workgroup size; 0: automatic (256 threads for slabs of up
  *                          to 12 KiB, else 512), or 256, 512
  *   COMBO_TUNE_SLAB_LDS_FLOOR slab kernel: least LDS bytes a launch asks for (0..65536); above

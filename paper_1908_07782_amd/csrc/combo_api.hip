@@ -130,20 +130,22 @@ int enqueue_round(float* dst, const float* src, const float* grad, float lr, int
         const uint64_t strips = ((uint64_t)P + (uint64_t)plan.cols - 1) / (uint64_t)plan.cols;
         if (strips > kMaxStrips) return COMBO_ERANGE;
         a.nstrips = (uint32_t)strips;
-        // Which strips a workgroup takes.  Workgroup ids go round-robin over the 8 XCDs, so with
-        // strip = id all XCDs move through the arena together; the alternative gives every XCD
-        // its own contiguous eighth.  Measured on MI355X: the eighths cost 2-10 % up to about
-        // 5 GiB per matrix and 10-15 % on row-major arenas at any size (the L2 -> fabric
-        // request stalls double to triple), but gain 2-8 % on tiled arenas from about 10 GiB
-        // per matrix on (16 x 335 M: 6.64 vs 6.79 ms).
+        // Which strips a workgroup takes.  Workgroup ids go round-robin over the 8 XCDs; with
+        // strip = id, XCD x only ever sees the tiles whose address bits just above the tile
+        // size equal x.  Letting the XCDs take turns at runs of 16 consecutive tiles (128 KiB
+        // for 8 KiB tiles) moves that pattern to higher address bits and measures 1.5-7 %
+        // faster on tiled arenas of every size tried (c2 6.35 -> 6.50, c5 6.29 -> 6.47, 64 x 80 M
+        // 6.14 -> 6.55 TB/s; runs of 4 or 8 tiles are 5-10 % slower than either, runs that
+        // are not powers of two lose 2-4 %, whole eighths lose 2-10 % below about 5 GiB per
+        // matrix).  Row-major arenas keep strip = id: runs of 4-8 strips gain 3-4 % on c2 and
+        // c3 but lose 3-6 % on c5, and longer runs lose everywhere (the L2 -> fabric request
+        // stalls double to triple).
         const int order = g_slab_order.load();
         const bool both_tiled = a.tile_shift != 0 && a.dst_tile_shift != 0;
-        const bool eighths = order == 2 || (order == 0 && both_tiled &&
-                                            (uint64_t)N * (uint64_t)P * sizeof(float) >= (8ull << 30));
-        if (eighths) a.strips_per_xcd = (a.nstrips + combo::kXcds - 1) / combo::kXcds;
-        // a grid dimension holds fewer than 2^32 work-items
-        const uint64_t groups = a.strips_per_xcd != 0 ? (uint64_t)combo::kXcds * a.strips_per_xcd : strips;
-        if (groups * (uint64_t)combo::slab_threads(N, plan.cols) > 0xFFFFFFFFull) return COMBO_ERANGE;
+        if (order == 2) a.strips_per_xcd = (a.nstrips + combo::kXcds - 1) / combo::kXcds;
+        else if (order >= 3) a.strips_per_xcd = (uint32_t)order;   // runs of this many strips
+        else if (order == 0 && both_tiled) a.strips_per_xcd = 16;
+        if (combo::slab_grid(a, plan.cols) == 0) return COMBO_ERANGE;   // work-items per grid dimension
     }
     a.hash_sr = hash_sr;
     if (hashed)
@@ -601,7 +603,7 @@ int combo_tune(int key, int value) {
             g_slab_cols.store(value);
             return COMBO_OK;
         case COMBO_TUNE_SLAB_ORDER:
-            if (value < 0 || value > 2) return COMBO_EINVAL;
+            if (value < 0 || value > (1 << 24)) return COMBO_EINVAL;
             g_slab_order.store(value);
             return COMBO_OK;
         case COMBO_TUNE_SLAB_THREADS:

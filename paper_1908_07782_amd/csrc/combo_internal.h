@@ -33,8 +33,8 @@ struct RoundArgs {
     int64_t dst_ld;          // back buffer: its own pitch and layout (normally the front buffer's)
     int32_t dst_tile_shift;
     uint32_t nstrips;        // slab kernels: ceil(P / strip width)
-    uint32_t strips_per_xcd; // slab kernels: 0: workgroup i takes strip i; else workgroup i takes strip
-                             // (i mod 8)*strips_per_xcd + i/8, a contiguous range of strips per XCD
+    uint32_t strips_per_xcd; // slab kernels: 0: workgroup i takes strip i; else the XCDs (i mod 8) take turns
+                             // at runs of this many consecutive strips
     uint64_t hash_sr;        // table-free rounds: peer-hash state after seed and round
 };
 

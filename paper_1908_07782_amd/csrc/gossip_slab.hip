@@ -98,15 +98,20 @@ int slab_strip_cols(int32_t N, int32_t R, int requested, bool hashed) {
     return slab_lds_bytes(N, R, 64, hashed) <= kLimit ? 64 : 0;
 }
 
-// workgroups of a slab launch: one per strip, or, with a contiguous range of strips per XCD,
-// 8 * strips_per_xcd (the surplus ones return at once); 0: beyond the grid limit
+// workgroups of a slab launch: one per strip, or, when the XCDs take turns at runs of
+// strips_per_xcd strips, whole rounds of 8 runs (the surplus workgroups return at once);
+// 0: beyond the grid limit
 uint32_t slab_grid(const RoundArgs& a, int W) {
     const uint64_t strips = ((uint64_t)a.P + (uint64_t)W - 1) / (uint64_t)W;
     if (strips > 0x7FFFFFF0ull || strips != a.nstrips) return 0;
-    const uint32_t grid = a.strips_per_xcd != 0 ? (uint32_t)kXcds * a.strips_per_xcd : a.nstrips;
+    uint64_t grid = strips;
+    if (a.strips_per_xcd != 0) {
+        const uint64_t round_strips = (uint64_t)kXcds * a.strips_per_xcd;
+        grid = (strips + round_strips - 1) / round_strips * round_strips;
+    }
     // a grid dimension holds fewer than 2^32 work-items
-    if ((uint64_t)grid * (uint64_t)slab_threads(a.N, W) > 0xFFFFFFFFull) return 0;
-    return grid;
+    if (grid * (uint64_t)slab_threads(a.N, W) > 0xFFFFFFFFull) return 0;
+    return (uint32_t)grid;
 }
 
 hipError_t launch_round_slab(const RoundArgs& a, int W, hipStream_t st) {

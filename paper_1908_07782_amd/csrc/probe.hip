@@ -24,9 +24,17 @@ constexpr int kProbeThreads = 256;
 // 128-bit word u (of FLIGHT) of a thread.  Strided: the words of a thread are a workgroup's
 // width (4 KiB) apart, so each of the FLIGHT instructions of a workgroup covers 4 KiB.
 // Adjacent: the FLIGHT instructions of one wavefront cover FLIGHT consecutive KiB.
+// `run` != 0: the workgroups of one XCD (ids congruent modulo 8) take turns at runs of `run`
+// consecutive blocks instead of every eighth block (see the strip order of the slab kernel).
+__device__ __forceinline__ uint32_t probe_block(uint32_t run) {
+    if (run == 0) return blockIdx.x;
+    const uint32_t turn = blockIdx.x >> 3, r = turn / run;
+    return (r * kXcds + (blockIdx.x & (kXcds - 1))) * run + (turn - r * run);
+}
+
 template <int FLIGHT, bool ADJACENT>
-__device__ __forceinline__ uint64_t probe_word(int u) {
-    const uint64_t base = (uint64_t)blockIdx.x * (kProbeThreads * FLIGHT);
+__device__ __forceinline__ uint64_t probe_word(int u, uint32_t run) {
+    const uint64_t base = (uint64_t)probe_block(run) * (kProbeThreads * FLIGHT);
     if (ADJACENT) {
         const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
         return base + (uint64_t)((wave * FLIGHT + u) * 64 + lane);
@@ -37,16 +45,16 @@ __device__ __forceinline__ uint64_t probe_word(int u) {
 template <int FLIGHT, bool ADJACENT>
 __global__ __launch_bounds__(kProbeThreads) void probe_copy_kernel(float* __restrict__ dst,
                                                                    const float* __restrict__ src,
-                                                                   uint64_t n4) {
+                                                                   uint64_t n4, uint32_t run) {
     v4f v[FLIGHT];
 #pragma unroll
     for (int u = 0; u < FLIGHT; ++u) {
-        const uint64_t i = probe_word<FLIGHT, ADJACENT>(u);
+        const uint64_t i = probe_word<FLIGHT, ADJACENT>(u, run);
         if (i < n4) v[u] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(src) + i);
     }
 #pragma unroll
     for (int u = 0; u < FLIGHT; ++u) {
-        const uint64_t i = probe_word<FLIGHT, ADJACENT>(u);
+        const uint64_t i = probe_word<FLIGHT, ADJACENT>(u, run);
         if (i < n4) __builtin_nontemporal_store(v[u], reinterpret_cast<v4f*>(dst) + i);
     }
 }
@@ -54,12 +62,12 @@ __global__ __launch_bounds__(kProbeThreads) void probe_copy_kernel(float* __rest
 template <int FLIGHT, bool ADJACENT>
 __global__ __launch_bounds__(kProbeThreads) void probe_read_kernel(float* __restrict__ dst,
                                                                    const float* __restrict__ src,
-                                                                   uint64_t n4) {
+                                                                   uint64_t n4, uint32_t run) {
     __shared__ float part[kProbeThreads];
     v4f v[FLIGHT];
 #pragma unroll
     for (int u = 0; u < FLIGHT; ++u) {
-        const uint64_t i = probe_word<FLIGHT, ADJACENT>(u);
+        const uint64_t i = probe_word<FLIGHT, ADJACENT>(u, run);
         v[u] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
         if (i < n4) v[u] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(src) + i);
     }
@@ -72,15 +80,16 @@ __global__ __launch_bounds__(kProbeThreads) void probe_read_kernel(float* __rest
         if ((int)threadIdx.x < half) part[threadIdx.x] += part[threadIdx.x + half];
         __syncthreads();
     }
-    if (threadIdx.x == 0) dst[blockIdx.x] = part[0];
+    const uint32_t block = probe_block(run);
+    if (threadIdx.x == 0 && (uint64_t)block * (kProbeThreads * FLIGHT) < n4) dst[block] = part[0];
 }
 
 template <int FLIGHT, bool ADJACENT>
-__global__ __launch_bounds__(kProbeThreads) void probe_write_kernel(float* __restrict__ dst, uint64_t n4) {
+__global__ __launch_bounds__(kProbeThreads) void probe_write_kernel(float* __restrict__ dst, uint64_t n4, uint32_t run) {
     const v4f c = v4f{1.0f, 2.0f, 3.0f, 4.0f};
 #pragma unroll
     for (int u = 0; u < FLIGHT; ++u) {
-        const uint64_t i = probe_word<FLIGHT, ADJACENT>(u);
+        const uint64_t i = probe_word<FLIGHT, ADJACENT>(u, run);
         if (i < n4) __builtin_nontemporal_store(c, reinterpret_cast<v4f*>(dst) + i);
     }
 }
@@ -135,7 +144,8 @@ __global__ __launch_bounds__(kProbeThreads) void probe_multi_read_kernel(float* 
 }  // namespace
 
 // kind: 0 linear copy, 1 read only, 2 write only (n = N*ld floats, `param` = 128-bit words in
-// flight per thread: 1, 2, 4 or 8; cols == 1: the words of a wavefront are adjacent); 3 row-chunk copy, 4 tile copy (`cols` columns per strip);
+// flight per thread: 1, 2, 4 or 8; cols bit 0: the words of a wavefront are adjacent; cols >> 4:
+// blocks per XCD turn); 3 row-chunk copy, 4 tile copy (`cols` columns per strip);
 // 5 multi-read pass (`param` = rows read per output).  Only whole 128-bit words, strips and
 // tiles are touched.  Returns hipErrorInvalidValue for shapes the probes do not cover.
 hipError_t launch_bandwidth_probe(int kind, float* dst, const float* src, int32_t N, int64_t ld, int64_t P,
@@ -144,10 +154,13 @@ hipError_t launch_bandwidth_probe(int kind, float* dst, const float* src, int32_
     if (kind >= 0 && kind <= 2) {
         if (param != 1 && param != 2 && param != 4 && param != 8) return hipErrorInvalidValue;
         const uint64_t per_wg = (uint64_t)kProbeThreads * (uint64_t)param;
-        const uint64_t grid64 = (n4 + per_wg - 1) / per_wg;
-        if (grid64 == 0 || grid64 > 0x7FFFFFFFull) return hipErrorInvalidValue;
+        uint64_t grid64 = (n4 + per_wg - 1) / per_wg;
+        const bool adjacent = (cols & 1) != 0;
+        const uint32_t run = (uint32_t)(cols >> 4);              // blocks per XCD turn, 0: block = id
+        if (run != 0) grid64 = (grid64 + 8ull * run - 1) / (8ull * run) * (8ull * run);   // surplus blocks are out of range
+        // a grid dimension holds fewer than 2^32 work-items
+        if (cols < 0 || grid64 == 0 || grid64 * kProbeThreads > 0xFFFFFFFFull) return hipErrorInvalidValue;
         const dim3 grid((uint32_t)grid64), block(kProbeThreads);
-        const bool adjacent = cols == 1;
 #define COMBO_PROBE_FLIGHT(KERNEL, ...)                                                                   \
         switch (param * 2 + (adjacent ? 1 : 0)) {                                                         \
             case 2: case 3: hipLaunchKernelGGL((KERNEL<1, false>), grid, block, 0, st, __VA_ARGS__); break; \
@@ -158,9 +171,9 @@ hipError_t launch_bandwidth_probe(int kind, float* dst, const float* src, int32_
             case 16: hipLaunchKernelGGL((KERNEL<8, false>), grid, block, 0, st, __VA_ARGS__); break;      \
             default: hipLaunchKernelGGL((KERNEL<8, true>), grid, block, 0, st, __VA_ARGS__); break;       \
         }
-        if (kind == 0) { COMBO_PROBE_FLIGHT(probe_copy_kernel, dst, src, n4) }
-        else if (kind == 1) { COMBO_PROBE_FLIGHT(probe_read_kernel, dst, src, n4) }
-        else { COMBO_PROBE_FLIGHT(probe_write_kernel, dst, n4) }
+        if (kind == 0) { COMBO_PROBE_FLIGHT(probe_copy_kernel, dst, src, n4, run) }
+        else if (kind == 1) { COMBO_PROBE_FLIGHT(probe_read_kernel, dst, src, n4, run) }
+        else { COMBO_PROBE_FLIGHT(probe_write_kernel, dst, n4, run) }
 #undef COMBO_PROBE_FLIGHT
         return hipGetLastError();
     }
