@@ -30,6 +30,8 @@ struct Layout {
 
 // the slab kernels' grid: one workgroup per strip, rounded up to a multiple of 8
 constexpr uint64_t kMaxStrips = 0x7FFFFFF0ull;
+// tiles per turn of an XCD in kernels that work tile by tile (see enqueue_round)
+constexpr uint32_t kTileRun = 16;
 
 int log2_of(int pow2) {
     int k = 0;
@@ -140,11 +142,12 @@ int enqueue_round(float* dst, const float* src, const float* grad, float lr, int
         // matrix).  Row-major arenas keep strip = id: runs of 4-8 strips gain 3-4 % on c2 and
         // c3 but lose 3-6 % on c5, and longer runs lose everywhere (the L2 -> fabric request
         // stalls double to triple).
+        // Rounds that change layout gain as well when one side is tiled (c2: +3-5 %).
         const int order = g_slab_order.load();
-        const bool both_tiled = a.tile_shift != 0 && a.dst_tile_shift != 0;
+        const bool any_tiled = a.tile_shift != 0 || a.dst_tile_shift != 0;
         if (order == 2) a.strips_per_xcd = (a.nstrips + combo::kXcds - 1) / combo::kXcds;
         else if (order >= 3) a.strips_per_xcd = (uint32_t)order;   // runs of this many strips
-        else if (order == 0 && both_tiled) a.strips_per_xcd = 16;
+        else if (order == 0 && any_tiled) a.strips_per_xcd = kTileRun;
         if (combo::slab_grid(a, plan.cols) == 0) return COMBO_ERANGE;   // work-items per grid dimension
     }
     a.hash_sr = hash_sr;
@@ -299,6 +302,16 @@ bool tile_cols_ok(int tile_cols) {
     return tile_cols >= 8 && tile_cols <= 1024 && (tile_cols & (tile_cols - 1)) == 0;
 }
 
+// Tile order of the conversion kernels, under the slab kernel's knob: the XCDs take turns at
+// runs of 16 tiles (measured against tile i to workgroup i: pack +2-7 %, unpack +3-6 % on c2
+// and c3, -2 % on c5).
+uint32_t relayout_run(uint64_t tiles) {
+    const int order = g_slab_order.load();
+    if (order == 1) return 0;
+    if (order == 2) return (uint32_t)((tiles + combo::kXcds - 1) / combo::kXcds);
+    return order >= 3 ? (uint32_t)order : kTileRun;
+}
+
 int64_t tiled_elems(int32_t N, int64_t P, int tile_cols) {
     return (P + tile_cols - 1) / tile_cols * (int64_t)N * (int64_t)tile_cols;
 }
@@ -348,7 +361,8 @@ int combo_pack_tiled(float* d_tiled, const float* d_rows, int64_t ld, int32_t N,
     if (overlaps(d_tiled, (uint64_t)tiled_elems(N, P, tile_cols) * 4, d_rows,
                  (uint64_t)N * (uint64_t)ld * 4))
         return COMBO_EALIAS;
-    return combo::launch_pack_tiled(d_tiled, d_rows, ld, N, P, tile_cols, (hipStream_t)stream) ==
+    return combo::launch_pack_tiled(d_tiled, d_rows, ld, N, P, tile_cols,
+                                    relayout_run(((uint64_t)P + tile_cols - 1) / tile_cols), (hipStream_t)stream) ==
                    hipSuccess ? COMBO_OK : COMBO_EHIP;
 }
 
@@ -360,7 +374,8 @@ int combo_unpack_tiled(float* d_rows, int64_t ld, const float* d_tiled, int32_t 
     if (overlaps(d_tiled, (uint64_t)tiled_elems(N, P, tile_cols) * 4, d_rows,
                  (uint64_t)N * (uint64_t)ld * 4))
         return COMBO_EALIAS;
-    return combo::launch_unpack_tiled(d_rows, ld, d_tiled, N, P, tile_cols, (hipStream_t)stream) ==
+    return combo::launch_unpack_tiled(d_rows, ld, d_tiled, N, P, tile_cols,
+                                    relayout_run(((uint64_t)P + tile_cols - 1) / tile_cols), (hipStream_t)stream) ==
                    hipSuccess ? COMBO_OK : COMBO_EHIP;
 }
 

@@ -72,10 +72,11 @@ hipError_t launch_divergence_tiles(double* dist2, double* workspace, const float
 hipError_t divergence_static_workspace(double** workspace, int64_t* bytes);
 
 // layout conversion kernels (layout.hip)
+// run: 0: workgroup i converts tile i; else the XCDs take turns at runs of `run` tiles
 hipError_t launch_pack_tiled(float* tiled, const float* rows, int64_t ld, int32_t N, int64_t P,
-                             int tile_cols, hipStream_t st);
+                             int tile_cols, uint32_t run, hipStream_t st);
 hipError_t launch_unpack_tiled(float* rows, int64_t ld, const float* tiled, int32_t N, int64_t P,
-                               int tile_cols, hipStream_t st);
+                               int tile_cols, uint32_t run, hipStream_t st);
 
 // gather-free passes with the kernels' memory access patterns (probe.hip)
 hipError_t launch_bandwidth_probe(int kind, float* dst, const float* src, int32_t N, int64_t ld, int64_t P,

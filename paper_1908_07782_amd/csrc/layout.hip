@@ -41,10 +41,17 @@ template <bool PACK>
 __global__ __launch_bounds__(kThreads) void relayout_vec_kernel(float* __restrict__ out,
                                                                 const float* __restrict__ in,
                                                                 int64_t ld, int32_t N, int64_t P,
-                                                                int Wt) {
-    const int64_t col0 = (int64_t)blockIdx.x * Wt;
+                                                                int Wt, uint32_t ntiles, uint32_t run) {
+    // which tile: workgroup i takes tile i, or the XCDs (i mod 8) take turns at runs of `run` tiles
+    uint32_t tile = blockIdx.x;
+    if (run != 0) {
+        const uint32_t turn = blockIdx.x >> 3, r = turn / run;
+        tile = (r * kXcds + (blockIdx.x & (kXcds - 1))) * run + (turn - r * run);
+        if (tile >= ntiles) return;
+    }
+    const int64_t col0 = (int64_t)tile * Wt;
     const int width = (int)(col0 + Wt <= P ? Wt : P - col0);
-    const size_t tile_base = (size_t)blockIdx.x * (size_t)N * (size_t)Wt;
+    const size_t tile_base = (size_t)tile * (size_t)N * (size_t)Wt;
     const int W4 = Wt >> 2;
     const int w4_shift = 31 - __clz(W4);
     const int total4 = N * W4;
@@ -84,14 +91,17 @@ __global__ __launch_bounds__(kThreads) void relayout_vec_kernel(float* __restric
 
 template <bool PACK>
 hipError_t launch_relayout(float* out, const float* in, int64_t ld, int32_t N, int64_t P, int Wt,
-                           hipStream_t st) {
+                           uint32_t run, hipStream_t st) {
     const uint64_t tiles = ((uint64_t)P + (uint64_t)Wt - 1) / (uint64_t)Wt;
-    if (tiles > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    uint64_t groups = tiles;
+    if (run != 0) groups = (tiles + 8ull * run - 1) / (8ull * run) * (8ull * run);
+    // a grid dimension holds fewer than 2^32 work-items
+    if (tiles > 0x7FFFFFF0ull || groups * kThreads > 0xFFFFFFFFull) return hipErrorInvalidValue;
     const bool vec = (((uintptr_t)out | (uintptr_t)in) & 15u) == 0 && ld % 4 == 0 && Wt % 4 == 0 &&
                      (Wt & (Wt - 1)) == 0;
     if (vec)
-        hipLaunchKernelGGL(relayout_vec_kernel<PACK>, dim3((uint32_t)tiles), dim3(kThreads), 0, st, out,
-                           in, ld, N, P, Wt);
+        hipLaunchKernelGGL(relayout_vec_kernel<PACK>, dim3((uint32_t)groups), dim3(kThreads), 0, st, out,
+                           in, ld, N, P, Wt, (uint32_t)tiles, run);
     else
         hipLaunchKernelGGL(relayout_kernel<PACK>, dim3((uint32_t)tiles), dim3(kThreads), 0, st, out, in,
                            ld, N, P, Wt);
@@ -101,13 +111,13 @@ hipError_t launch_relayout(float* out, const float* in, int64_t ld, int32_t N, i
 }  // namespace
 
 hipError_t launch_pack_tiled(float* tiled, const float* rows, int64_t ld, int32_t N, int64_t P,
-                             int Wt, hipStream_t st) {
-    return launch_relayout<true>(tiled, rows, ld, N, P, Wt, st);
+                             int Wt, uint32_t run, hipStream_t st) {
+    return launch_relayout<true>(tiled, rows, ld, N, P, Wt, run, st);
 }
 
 hipError_t launch_unpack_tiled(float* rows, int64_t ld, const float* tiled, int32_t N, int64_t P,
-                               int Wt, hipStream_t st) {
-    return launch_relayout<false>(rows, tiled, ld, N, P, Wt, st);
+                               int Wt, uint32_t run, hipStream_t st) {
+    return launch_relayout<false>(rows, tiled, ld, N, P, Wt, run, st);
 }
 
 }  // namespace combo
