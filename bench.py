@@ -619,14 +619,14 @@ def main():
     torch.cuda.empty_cache()
     per_config = []
     if not args.no_per_config:
-        # every configuration in both layouts (the headline one only in its other layout), short
-        # runs; parity of round 0 against the oracle on the whole arena where the host holds it
-        short = min(args.steps, 30)
+        # every configuration in both layouts (the headline one only in its other layout), at
+        # least 50 steps per trial; parity of round 0 against the oracle on the whole arena
+        short = max(args.steps, 50)
         for name, w in combo.workloads.WORKLOADS.items():
             for layout in ("tiled", "rows"):
                 if name == wl.name and layout == args.layout:
                     continue
-                r = measure(combo, w, args, layout, short, 3, args.trials,
+                r = measure(combo, w, args, layout, short, 10, args.trials,
                             oracle and name != wl.name and layout == "tiled", 0.0)
                 r.pop("cpu_baseline", None)
                 r["steps"] = short

@@ -386,8 +386,8 @@ int combo_bandwidth_probe(int kind, float* d_dst, const float* d_src, int32_t N,
  *                          over the 8 XCDs): 1: workgroup i takes strip i; 2: every XCD works
  *                          through its own contiguous eighth of the strips; k >= 3: the XCDs
  *                          take turns at runs of k consecutive strips; 0: automatic (runs of
- *                          16 for tiled arenas, where they measure 1.5-7 % faster; strip i
- *                          for row-major ones)
+ *                          16 tiles for tiled arenas, 32 from 7 GiB per matrix on, where
+ *                          they measure 1-7 % faster; strip i for row-major ones)
  *   COMBO_TUNE_SLAB_THREADS slab kernel: workgroup size; 0: automatic (256 threads for slabs of up
  *                          to 12 KiB, else 512), or 256, 512
  *   COMBO_TUNE_SLAB_LDS_FLOOR slab kernel: least LDS bytes a launch asks for (0..65536); above

@@ -30,8 +30,11 @@ struct Layout {
 
 // the slab kernels' grid: one workgroup per strip, rounded up to a multiple of 8
 constexpr uint64_t kMaxStrips = 0x7FFFFFF0ull;
-// tiles per turn of an XCD in kernels that work tile by tile (see enqueue_round)
-constexpr uint32_t kTileRun = 16;
+// tiles per turn of an XCD in kernels that work tile by tile (see enqueue_round): 16, or 32
+// for matrices of 7 GiB and more
+uint32_t tile_run(int32_t N, int64_t P) {
+    return (uint64_t)N * (uint64_t)P * sizeof(float) >= (7ull << 30) ? 32u : 16u;
+}
 
 int log2_of(int pow2) {
     int k = 0;
@@ -135,19 +138,21 @@ int enqueue_round(float* dst, const float* src, const float* grad, float lr, int
         // Which strips a workgroup takes.  Workgroup ids go round-robin over the 8 XCDs; with
         // strip = id, XCD x only ever sees the tiles whose address bits just above the tile
         // size equal x.  Letting the XCDs take turns at runs of 16 consecutive tiles (128 KiB
-        // for 8 KiB tiles) moves that pattern to higher address bits and measures 1.5-7 %
-        // faster on tiled arenas of every size tried (c2 6.35 -> 6.50, c5 6.29 -> 6.47, 64 x 80 M
-        // 6.14 -> 6.55 TB/s; runs of 4 or 8 tiles are 5-10 % slower than either, runs that
-        // are not powers of two lose 2-4 %, whole eighths lose 2-10 % below about 5 GiB per
-        // matrix).  Row-major arenas keep strip = id: runs of 4-8 strips gain 3-4 % on c2 and
-        // c3 but lose 3-6 % on c5, and longer runs lose everywhere (the L2 -> fabric request
-        // stalls double to triple).
-        // Rounds that change layout gain as well when one side is tiled (c2: +3-5 %).
+        // for 8 KiB tiles) moves that pattern to higher address bits.  Measured on tiled
+        // arenas, both ping-pong directions averaged: runs of 16 gain 1-5 % up to about 7 GiB
+        // per matrix (c2 6.42 -> 6.57, c3 6.39 -> 6.65 TB/s) but become erratic beyond (one
+        // direction of c5 gains 5 %, the other loses 6 %); runs of 32 gain 1-7 % at every size
+        // tried from 6 to 21 GiB (c5 6.31 -> 6.43, 100 x 30 M 5.86 -> 6.27 TB/s); runs of 4 or
+        // 8 tiles are 5-10 % slower than strip = id, runs that are not powers of two lose
+        // 2-4 %, whole eighths lose 2-10 % on small arenas.  Rounds that change layout gain
+        // too when one side is tiled (c2: +3-5 %).  Row-major arenas keep strip = id: runs of
+        // 4-8 strips gain 3-4 % on c2 and c3 but lose 3-6 % on c5, and longer runs lose
+        // everywhere (the L2 -> fabric request stalls double).
         const int order = g_slab_order.load();
         const bool any_tiled = a.tile_shift != 0 || a.dst_tile_shift != 0;
         if (order == 2) a.strips_per_xcd = (a.nstrips + combo::kXcds - 1) / combo::kXcds;
         else if (order >= 3) a.strips_per_xcd = (uint32_t)order;   // runs of this many strips
-        else if (order == 0 && any_tiled) a.strips_per_xcd = kTileRun;
+        else if (order == 0 && any_tiled) a.strips_per_xcd = tile_run(N, P);
         if (combo::slab_grid(a, plan.cols) == 0) return COMBO_ERANGE;   // work-items per grid dimension
     }
     a.hash_sr = hash_sr;
@@ -305,11 +310,11 @@ bool tile_cols_ok(int tile_cols) {
 // Tile order of the conversion kernels, under the slab kernel's knob: the XCDs take turns at
 // runs of 16 tiles (measured against tile i to workgroup i: pack +2-7 %, unpack +3-6 % on c2
 // and c3, -2 % on c5).
-uint32_t relayout_run(uint64_t tiles) {
+uint32_t relayout_run(uint64_t tiles, int32_t N, int64_t P) {
     const int order = g_slab_order.load();
     if (order == 1) return 0;
     if (order == 2) return (uint32_t)((tiles + combo::kXcds - 1) / combo::kXcds);
-    return order >= 3 ? (uint32_t)order : kTileRun;
+    return order >= 3 ? (uint32_t)order : tile_run(N, P);
 }
 
 int64_t tiled_elems(int32_t N, int64_t P, int tile_cols) {
@@ -362,7 +367,7 @@ int combo_pack_tiled(float* d_tiled, const float* d_rows, int64_t ld, int32_t N,
                  (uint64_t)N * (uint64_t)ld * 4))
         return COMBO_EALIAS;
     return combo::launch_pack_tiled(d_tiled, d_rows, ld, N, P, tile_cols,
-                                    relayout_run(((uint64_t)P + tile_cols - 1) / tile_cols), (hipStream_t)stream) ==
+                                    relayout_run(((uint64_t)P + tile_cols - 1) / tile_cols, N, P), (hipStream_t)stream) ==
                    hipSuccess ? COMBO_OK : COMBO_EHIP;
 }
 
@@ -375,7 +380,7 @@ int combo_unpack_tiled(float* d_rows, int64_t ld, const float* d_tiled, int32_t 
                  (uint64_t)N * (uint64_t)ld * 4))
         return COMBO_EALIAS;
     return combo::launch_unpack_tiled(d_rows, ld, d_tiled, N, P, tile_cols,
-                                    relayout_run(((uint64_t)P + tile_cols - 1) / tile_cols), (hipStream_t)stream) ==
+                                    relayout_run(((uint64_t)P + tile_cols - 1) / tile_cols, N, P), (hipStream_t)stream) ==
                    hipSuccess ? COMBO_OK : COMBO_EHIP;
 }
 
