@@ -390,9 +390,11 @@ int combo_bandwidth_probe(int kind, float* d_dst, const float* d_src, int32_t N,
  *                          they measure 1-7 % faster; strip i for row-major ones)
  *   COMBO_TUNE_SLAB_THREADS slab kernel: workgroup size; 0: automatic (256 threads for slabs of up
  *                          to 12 KiB, else 512), or 256, 512
- *   COMBO_TUNE_SLAB_LDS_FLOOR slab kernel: least LDS bytes a launch asks for (0..65536); above
+ *   COMBO_TUNE_SLAB_LDS_FLOOR slab kernel: least LDS bytes a launch asks for (1..65536); above
  *                          what the kernel uses it only lowers the number of workgroups
- *                          resident per compute unit
+ *                          resident per compute unit; 0: automatic (24 KiB for 256-thread
+ *                          workgroups of uniform-weight static rounds with R <= 4 on arenas
+ *                          below 7 GiB per matrix, where six resident workgroups beat eight)
  *   COMBO_TUNE_TILE_COLS   row-tile kernel: columns of one worker handled by one
  *                          workgroup: 0 = automatic (2048, or 1024 for more than 384
  *                          workers), or 1024, 2048, 4096

@@ -94,7 +94,7 @@ hipError_t launch_round_slab_dynamic(const RoundArgs& a, int strip_cols, uint32_
                                      hipStream_t st);
 size_t slab_lds_bytes(int32_t N, int32_t R, int strip_cols, bool hashed);
 uint32_t slab_grid(const RoundArgs& a, int strip_cols);
-size_t slab_lds_request(int32_t N, int32_t R, int strip_cols, bool hashed);
+size_t slab_lds_request(const RoundArgs& a, int strip_cols, bool hashed);
 void set_slab_lds_floor(int bytes);   // least LDS a slab launch asks for (limits resident workgroups)
 int get_slab_lds_floor();
 int slab_threads(int32_t N, int strip_cols);

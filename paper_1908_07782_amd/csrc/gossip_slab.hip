@@ -24,20 +24,24 @@ int slab_threads(int32_t N, int W) {
 
 // LDS to ask for at launch: at least what the kernel uses.  Asking for more lowers the number
 // of workgroups resident per compute unit (160 KiB of LDS each).  Measured on MI355X with
-// 256-thread workgroups and 8 KiB slabs: six resident workgroups (23..26 KiB each) stream
-// 1-2.5 % faster than the eight that the wavefront limit allows (c5: 6.79 vs 6.93 ms; fewer
-// requests competing in the memory system), five or fewer are slower (c5: 7.72 ms).  That holds
-// while the aggregation phase is short: from R = 8 on the two extra workgroups are worth more
-// for hiding it (30 workers, R = 8: 1.03 vs 1.05 ms, R = 16: 1.17 vs 1.22 ms), so the rule
-// applies up to R = 4.  512-thread workgroups are four per compute unit anyway.  The knob:
-// 0 = this rule, else the floor in bytes.
+// 256-thread workgroups and 8 KiB slabs, uniform weights, R <= 4: six resident workgroups
+// (23..26 KiB each) stream up to 3 % faster than the eight that the wavefront limit allows on
+// arenas below about 7 GiB per matrix (c3: 1.00 vs 1.03 ms; fewer requests competing in the
+// memory system; c2 and c4 unchanged), five or fewer are slower (c5: 7.72 vs 6.93 ms).  It
+// does not hold where a workgroup spends longer between its loads and its stores: with
+// dataset-size weights or dynamic workers the two extra workgroups are worth 8-10 % (c2
+// weighted: 0.49 vs 0.55 ms), from R = 8 on 2-5 %, and on the largest arena 1 %.  512-thread
+// workgroups are four per compute unit anyway.  The knob: 0 = this rule, else the floor in bytes.
 std::atomic<int> g_slab_lds_floor{0};
 void set_slab_lds_floor(int bytes) { g_slab_lds_floor.store(bytes); }
 int get_slab_lds_floor() { return g_slab_lds_floor.load(); }
-size_t slab_lds_request(int32_t N, int32_t R, int W, bool hashed) {
-    const size_t used = slab_lds_bytes(N, R, W, hashed);
+size_t slab_lds_request(const RoundArgs& a, int W, bool hashed) {
+    const size_t used = slab_lds_bytes(a.N, a.R, W, hashed);
     size_t floor_bytes = (size_t)g_slab_lds_floor.load();
-    if (floor_bytes == 0 && slab_threads(N, W) == 256 && R <= 4) floor_bytes = 24 * 1024;
+    const bool short_aggregation = a.R <= 4 && a.dsz == nullptr && a.status == nullptr;
+    const bool small_arena = (uint64_t)a.N * (uint64_t)a.P * sizeof(float) < (7ull << 30);
+    if (floor_bytes == 0 && slab_threads(a.N, W) == 256 && short_aggregation && small_arena)
+        floor_bytes = 24 * 1024;
     return used > floor_bytes ? used : floor_bytes;
 }
 
@@ -117,7 +121,7 @@ uint32_t slab_grid(const RoundArgs& a, int W) {
 hipError_t launch_round_slab(const RoundArgs& a, int W, hipStream_t st) {
     const uint32_t grid = slab_grid(a, W);
     if (grid == 0) return hipErrorInvalidValue;
-    const size_t lds = slab_lds_request(a.N, a.R, W, false);
+    const size_t lds = slab_lds_request(a, W, false);
     if (a.status != nullptr) return launch_round_slab_dynamic(a, W, grid, lds, st);
     switch (a.R) {
         case 0: return launch_rt<0>(a, W, grid, lds, st);

@@ -37,7 +37,7 @@ hipError_t launch_hashed_rt(const RoundArgs& a, int W, uint32_t grid, size_t lds
 hipError_t launch_round_slab_hashed(const RoundArgs& a, int W, hipStream_t st) {
     const uint32_t grid = slab_grid(a, W);
     if (grid == 0) return hipErrorInvalidValue;
-    const size_t lds = slab_lds_request(a.N, a.R, W, true);
+    const size_t lds = slab_lds_request(a, W, true);
     switch (a.R) {
         case 0: return launch_hashed_rt<0>(a, W, grid, lds, st);
         case 1: return launch_hashed_rt<1>(a, W, grid, lds, st);
