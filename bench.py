@@ -156,7 +156,7 @@ def extras(combo, wl):
         emit(f"probe: flat copy, {flight} words in flight, XCD runs of {run} blocks (128 KiB)", time_kernel(
             lambda: combo.bandwidth_probe(combo.PROBE_COPY, arena[1], arena[0], P, cols=run << 4, param=flight,
                                           stream=stream), stream), 2 * foot, note="bytes = read + write")
-    for flight in (4, 8):
+    for flight in (1, 2, 4, 8):
         emit(f"probe: read only, {flight} words in flight", time_kernel(
             lambda: combo.bandwidth_probe(combo.PROBE_READ, arena[1], arena[0], P, param=flight, stream=stream),
             stream), foot, note="bytes = read")
