@@ -13,14 +13,6 @@
 namespace combo {
 namespace {
 
-constexpr uint64_t kGamma = kHashGamma;
-
-__device__ __forceinline__ uint64_t finalise(uint64_t z) { return hash_finalise(z); }
-
-__device__ __forceinline__ uint64_t take_in(uint64_t h, uint64_t counter) {
-    return hash_take_in(h, counter);
-}
-
 __global__ __launch_bounds__(64) void peer_table_kernel(int32_t* __restrict__ peers, int32_t N,
                                                         int32_t S, int32_t R, uint64_t seed,
                                                         uint64_t round) {
@@ -34,13 +26,13 @@ __global__ __launch_bounds__(64) void peer_table_kernel(int32_t* __restrict__ pe
     __syncthreads();
 
     if (threadIdx.x == 0) {
-        uint64_t h = finalise(seed + kGamma);
-        h = take_in(h, round);
-        h = take_in(h, (uint64_t)w);
-        h = take_in(h, (uint64_t)s);
+        uint64_t h = hash_finalise(seed + kHashGamma);
+        h = hash_take_in(h, round);
+        h = hash_take_in(h, (uint64_t)w);
+        h = hash_take_in(h, (uint64_t)s);
         int32_t* out = peers + (size_t)pair * (size_t)R;
         for (int32_t j = 0; j < R; ++j) {
-            const uint64_t word = take_in(h, (uint64_t)j);
+            const uint64_t word = hash_take_in(h, (uint64_t)j);
             const uint32_t span = (uint32_t)(M - j);
             const int32_t r = j + (int32_t)(((word >> 32) * (uint64_t)span) >> 32);
             const int32_t picked = cand[r];
@@ -71,18 +63,18 @@ __global__ __launch_bounds__(64) void peer_table_pooled_kernel(int32_t* __restri
     uint16_t* partner = pool_lds + M;            // [M] swap partner of every shuffle step
     const int32_t w = (int32_t)blockIdx.x;
     const int lane = (int)threadIdx.x;
-    uint64_t hw = finalise((seed ^ kPoolTag) + kGamma);
-    hw = take_in(hw, round);
-    hw = take_in(hw, (uint64_t)w);
+    uint64_t hw = hash_finalise((seed ^ kPoolTag) + kHashGamma);
+    hw = hash_take_in(hw, round);
+    hw = hash_take_in(hw, (uint64_t)w);
 
     const int64_t requests = (int64_t)S * R;
     const int64_t epochs = (requests + M - 1) / M;
     int64_t served = 0;                           // lane 0: requests done so far
     for (int64_t epoch = 0; epoch < epochs; ++epoch) {
-        const uint64_t he = take_in(hw, (uint64_t)epoch);
+        const uint64_t he = hash_take_in(hw, (uint64_t)epoch);
         for (int32_t i = lane; i < M; i += 64) {
             queue[i] = (uint16_t)(i + (i >= w ? 1 : 0));
-            const uint64_t word = take_in(he, (uint64_t)i);
+            const uint64_t word = hash_take_in(he, (uint64_t)i);
             partner[i] = (uint16_t)(i + (int32_t)(((word >> 32) * (uint64_t)(uint32_t)(M - i)) >> 32));
         }
         __syncthreads();
@@ -147,9 +139,9 @@ __global__ __launch_bounds__(64) void peer_table_pooled_wave_kernel(int32_t* __r
     const int32_t M = N - 1;                      // 1..64 candidates
     const int32_t w = (int32_t)blockIdx.x;
     const int lane = (int)threadIdx.x;
-    uint64_t hw = finalise((seed ^ kPoolTag) + kGamma);
-    hw = take_in(hw, round);
-    hw = take_in(hw, (uint64_t)w);
+    uint64_t hw = hash_finalise((seed ^ kPoolTag) + kHashGamma);
+    hw = hash_take_in(hw, round);
+    hw = hash_take_in(hw, (uint64_t)w);
 
     const int64_t requests = (int64_t)S * R;
     int32_t* out = peers + (size_t)w * (size_t)S * (size_t)R;
@@ -157,10 +149,10 @@ __global__ __launch_bounds__(64) void peer_table_pooled_wave_kernel(int32_t* __r
     int32_t j = 0;                                // position of the next request in its segment
     int32_t cpick = -1;                           // lane k: k-th pick of the segment in progress
     for (int64_t epoch = 0; served < requests; ++epoch) {
-        const uint64_t he = take_in(hw, (uint64_t)epoch);
+        const uint64_t he = hash_take_in(hw, (uint64_t)epoch);
         int32_t partner = lane;
         if (lane < M) {
-            const uint64_t word = take_in(he, (uint64_t)lane);
+            const uint64_t word = hash_take_in(he, (uint64_t)lane);
             partner = lane + (int32_t)(((word >> 32) * (uint64_t)(uint32_t)(M - lane)) >> 32);
         }
         int32_t where = lane;                     // position of the element that starts in this lane
@@ -239,13 +231,13 @@ __global__ __launch_bounds__(64) void peer_table_dynamic_kernel(int32_t* __restr
     __syncthreads();
 
     if (lane == 0) {
-        uint64_t h = finalise(seed + kGamma);
-        h = take_in(h, round);
-        h = take_in(h, (uint64_t)w);
-        h = take_in(h, (uint64_t)s);
+        uint64_t h = hash_finalise(seed + kHashGamma);
+        h = hash_take_in(h, round);
+        h = hash_take_in(h, (uint64_t)w);
+        h = hash_take_in(h, (uint64_t)s);
         const int32_t take = R < count ? R : count;
         for (int32_t j = 0; j < take; ++j) {
-            const uint64_t word = take_in(h, (uint64_t)j);
+            const uint64_t word = hash_take_in(h, (uint64_t)j);
             const int32_t r = j + (int32_t)(((word >> 32) * (uint64_t)(uint32_t)(count - j)) >> 32);
             const int32_t picked = cand[r];
             cand[r] = cand[j];

@@ -43,3 +43,19 @@ def test_bench_prints_one_json_line_with_the_required_fields():
     assert p["columns_checked"] == p["of_columns"] == 65536
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["cores"] == 1 and c["value"] > 0 and c["sample"] and c["cpu_model"]
+
+
+def test_committed_counter_profiles_match_the_kernel_sources():
+    """roofline.traffic is taken from the committed rocprofv3 --pmc summaries only while the
+    digest of the kernel sources stored in them is current: a kernel edit without a fresh
+    counter run would silently turn the field into null."""
+    sys.path.insert(0, ROOT)
+    import bench
+    for wl, layout in (("c5_bertlarge", "tiled"), ("c5_bertlarge", "rows"), ("c2_resnet18", "tiled"),
+                       ("c2_resnet18", "rows"), ("c3_resnet50", "tiled"), ("c4_prime_fused", "tiled")):
+        nbytes, source = bench.recorded_traffic(wl, layout)
+        assert nbytes is not None and os.path.exists(os.path.join(ROOT, source)), (wl, layout)
+        from paper_1908_07782_amd.workloads import WORKLOADS
+        w = WORKLOADS[wl]
+        compulsory = (12 if w.fused else 8) * w.N * w.P
+        assert abs(nbytes / compulsory - 1.0) < 0.01, (wl, layout, nbytes, compulsory)
