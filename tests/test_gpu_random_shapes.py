@@ -1,5 +1,7 @@
 """Randomised GPU-vs-oracle parity: 84 seeded random shapes (N, P, S, R, pitch, layout,
-weights, fused steps, dynamic status), each compared bit for bit with the CPU oracle."""
+weights, fused steps, dynamic status) through the single-layout entry points and 72 more through
+the round between layouts under random performance knobs, each compared bit for bit with the CPU
+oracle."""
 import numpy as np
 import pytest
 import torch
@@ -103,3 +105,68 @@ def test_random_case(combo, ref, case):
     assert np.array_equal(peers.cpu().numpy()[:N * S * R].reshape(T.shape), T)
     assert np.all(np.abs(got - want) <= 1e-6 * np.maximum(np.abs(want), 1e-30))
     assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+
+
+@pytest.mark.parametrize("case", range(72))
+def test_random_case_between_layouts_and_under_random_knobs(combo, ref, case):
+    """Random shapes through combo_round_relayout (any pair of layouts), with many short
+    segments, up to 20 replicas, and the performance knobs (strip order, workgroup size, LDS
+    floor) set at random: results never depend on them."""
+    from tests.test_gpu_relayout import Side, bits
+    from tests.test_gpu_tiled import np_pack
+    rng = np.random.default_rng(5000 + case)
+    N = int(rng.choice([2, 3, 5, 8, 16, 21, 32, 33, 64, 100]))
+    P = int(rng.choice([64, 65, 1000, 4097, 20_011, 65_536, 100_003]))
+    S = int(rng.choice([1, 2, 7, min(P, 40), min(P, 333), min(P, 5000), P]))
+    R = int(rng.integers(0, min(N - 1, 20) + 1))
+    mode = rng.choice(["plain", "weighted", "fused", "dynamic", "dynamic+weights"])
+    src_l, dst_l = rng.choice(["rows", "tiled"]), rng.choice(["rows", "tiled"])
+    seed, rnd = int(rng.integers(0, 2**63)), int(rng.integers(0, 2**20))
+    tau = int(rng.integers(1, 3)) if mode == "fused" else 0
+    order = int(rng.choice([0, 1, 2, 5, 16]))
+    threads = int(rng.choice([0, 256, 512]))
+    floor = int(rng.choice([0, 1, 32 * 1024]))
+    print(f"case {case}: N={N} P={P} S={S} R={R} {mode} {src_l}->{dst_l} tau={tau} order={order} "
+          f"threads={threads} floor={floor}", flush=True)
+    Xh = rng.normal(0, 0.05, (N, P)).astype(np.float32)
+    Gh = rng.normal(0, 1e-2, (tau, N, P)).astype(np.float32)
+    d_h = rng.integers(100, 2000, N).astype(np.float32) if "weight" in mode else None
+    status = rng.integers(0, 3, N).astype(np.uint8) if mode.startswith("dynamic") else None
+    if status is not None:
+        T = ref.make_peer_table_dynamic(status, N, S, R, seed, rnd)
+        want = ref.gossip_round_dynamic(Xh, T, status, P, S, R, d=d_h)
+    else:
+        T = ref.make_peer_table(N, S, R, seed, rnd)
+        want = ref.local_sgd_steps_then_gossip(Xh.copy(), Gh, 0.05, T, P, S, R) if tau \
+            else ref.gossip_round(Xh, T, P, S, R, d=d_h)
+
+    Wt = combo.tiled_cols(N, R)
+    src = Side(combo, N, P, Wt if src_l == "tiled" else 0, Xh)
+    dst = Side(combo, N, P, Wt if dst_l == "tiled" else 0, None, extra_pitch=int(rng.choice([0, 4, 64])))
+    grads = None
+    if tau:
+        if src.tile:
+            grads = torch.stack([torch.from_numpy(np.nan_to_num(np_pack(Gh[k], Wt))).cuda() for k in range(tau)])
+        else:
+            grads = torch.zeros((tau,) + tuple(src.t.shape), dtype=torch.float32, device="cuda")
+            grads[:, :, :P] = torch.from_numpy(Gh).cuda()
+    peers = torch.from_numpy(np.ascontiguousarray(T).reshape(-1)).cuda() if R else None
+    d = None if d_h is None else torch.from_numpy(d_h).cuda()
+    st = None if status is None else torch.from_numpy(status).cuda()
+    try:
+        combo.tune(combo.TUNE_SLAB_ORDER, order)
+        combo.tune(combo.TUNE_SLAB_THREADS, threads)
+        combo.tune(combo.TUNE_SLAB_LDS_FLOOR, floor)
+        combo.round_relayout(dst.t, dst.tile, src.t, src.tile, peers, N, P, S, R, grads=grads, lr=0.05,
+                             dataset_sizes=d, status=st)
+        torch.cuda.synchronize()
+    finally:
+        combo.tune(combo.TUNE_SLAB_ORDER, 0)
+        combo.tune(combo.TUNE_SLAB_THREADS, 0)
+        combo.tune(combo.TUNE_SLAB_LDS_FLOOR, 0)
+    got, pad_ok = dst.values()
+    nan_ok = np.array_equal(np.isnan(got), np.isnan(want))
+    assert nan_ok and pad_ok
+    ok = ~np.isnan(want)
+    assert np.array_equal(bits(got)[ok], bits(want)[ok])
+    assert np.array_equal(bits(src.values()[0]), bits(Xh))
