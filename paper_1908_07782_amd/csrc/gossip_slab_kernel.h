@@ -185,13 +185,8 @@ __global__ __launch_bounds__(kSlabThreads) void gossip_slab_kernel(const RoundAr
     // which strip: workgroup i takes strip i, or - workgroup ids go round-robin over the 8
     // XCDs - the XCDs take turns at runs of strips_per_xcd consecutive strips (with
     // strips_per_xcd = ceil(nstrips / 8) every XCD works through its own contiguous eighth)
-    uint32_t strip = blockIdx.x;
-    if (a.strips_per_xcd != 0) {
-        const uint32_t turn = blockIdx.x >> 3;                    // this XCD's turn-th workgroup
-        const uint32_t run = turn / a.strips_per_xcd;
-        strip = (run * kXcds + (blockIdx.x & (kXcds - 1))) * a.strips_per_xcd + (turn - run * a.strips_per_xcd);
-        if (strip >= a.nstrips) return;             // uniform for the workgroup
-    }
+    const uint32_t strip = xcd_run_block(blockIdx.x, a.strips_per_xcd);
+    if (strip >= a.nstrips) return;                 // surplus workgroup of the last round of runs; uniform
     const int64_t col0 = (int64_t)strip * W;
     const int64_t col_end = col0 + W < a.P ? col0 + W : a.P;
     // where the strip's row chunks live: row-major rows are ld apart and start at col0;

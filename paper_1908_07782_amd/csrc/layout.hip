@@ -43,12 +43,8 @@ __global__ __launch_bounds__(kThreads) void relayout_vec_kernel(float* __restric
                                                                 int64_t ld, int32_t N, int64_t P,
                                                                 int Wt, uint32_t ntiles, uint32_t run) {
     // which tile: workgroup i takes tile i, or the XCDs (i mod 8) take turns at runs of `run` tiles
-    uint32_t tile = blockIdx.x;
-    if (run != 0) {
-        const uint32_t turn = blockIdx.x >> 3, r = turn / run;
-        tile = (r * kXcds + (blockIdx.x & (kXcds - 1))) * run + (turn - r * run);
-        if (tile >= ntiles) return;
-    }
+    const uint32_t tile = xcd_run_block(blockIdx.x, run);
+    if (tile >= ntiles) return;
     const int64_t col0 = (int64_t)tile * Wt;
     const int width = (int)(col0 + Wt <= P ? Wt : P - col0);
     const size_t tile_base = (size_t)tile * (size_t)N * (size_t)Wt;

@@ -26,11 +26,7 @@ constexpr int kProbeThreads = 256;
 // Adjacent: the FLIGHT instructions of one wavefront cover FLIGHT consecutive KiB.
 // `run` != 0: the workgroups of one XCD (ids congruent modulo 8) take turns at runs of `run`
 // consecutive blocks instead of every eighth block (see the strip order of the slab kernel).
-__device__ __forceinline__ uint32_t probe_block(uint32_t run) {
-    if (run == 0) return blockIdx.x;
-    const uint32_t turn = blockIdx.x >> 3, r = turn / run;
-    return (r * kXcds + (blockIdx.x & (kXcds - 1))) * run + (turn - r * run);
-}
+__device__ __forceinline__ uint32_t probe_block(uint32_t run) { return xcd_run_block(blockIdx.x, run); }
 
 template <int FLIGHT, bool ADJACENT>
 __device__ __forceinline__ uint64_t probe_word(int u, uint32_t run) {

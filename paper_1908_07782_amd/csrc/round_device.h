@@ -164,6 +164,16 @@ __device__ __forceinline__ void draw_peers(uint64_t h_sr, int32_t w, int32_t s, 
     picks_from_partners(partner, w, R, out);
 }
 
+// Which block of work (strip, tile, chunk) workgroup `id` takes.  Workgroup ids go round-robin
+// over the 8 XCDs; with run == 0 block = id, so XCD x gets every eighth block; else the XCDs take
+// turns at runs of `run` consecutive blocks (block ids beyond the work are the caller's to skip).
+__device__ __forceinline__ uint32_t xcd_run_block(uint32_t id, uint32_t run) {
+    if (run == 0) return id;
+    const uint32_t turn = id >> 3;                    // the XCD's turn-th workgroup
+    const uint32_t r = turn / run;
+    return (r * kXcds + (id & (kXcds - 1))) * run + (turn - r * run);
+}
+
 // segment of column e: floor(e / L), the last segment also owning the remainder (Eq. 1)
 __device__ __forceinline__ int32_t segment_of(int64_t e, const RoundArgs& a) {
     uint64_t q;
