@@ -151,11 +151,14 @@ def extras(combo, wl):
             lambda: combo.bandwidth_probe(combo.PROBE_COPY, arena[1], arena[0], P, param=flight, stream=stream),
             stream), 2 * foot, note="bytes = read + write")
     for flight in (1, 2):
-        # the same copy with the XCDs taking turns at runs of 128 KiB of consecutive blocks
-        run = 128 * 1024 // (4096 * flight)
-        emit(f"probe: flat copy, {flight} words in flight, XCD runs of {run} blocks (128 KiB)", time_kernel(
-            lambda: combo.bandwidth_probe(combo.PROBE_COPY, arena[1], arena[0], P, cols=run << 4, param=flight,
-                                          stream=stream), stream), 2 * foot, note="bytes = read + write")
+        # the same passes with the XCDs taking turns at runs of 512 KiB of consecutive blocks
+        run = 512 * 1024 // (4096 * flight)
+        for kind, what, nbytes in ((combo.PROBE_COPY, "flat copy", 2 * foot), (combo.PROBE_READ, "read only", foot),
+                                   (combo.PROBE_WRITE, "write only", foot)):
+            emit(f"probe: {what}, {flight} words in flight, XCD runs of {run} blocks (512 KiB)", time_kernel(
+                lambda: combo.bandwidth_probe(kind, arena[1], None if kind == combo.PROBE_WRITE else arena[0], P,
+                                              cols=run << 4, param=flight, stream=stream), stream), nbytes,
+                note="bytes as for the plain probe")
     for flight in (1, 2, 4, 8):
         emit(f"probe: read only, {flight} words in flight", time_kernel(
             lambda: combo.bandwidth_probe(combo.PROBE_READ, arena[1], arena[0], P, param=flight, stream=stream),

@@ -120,6 +120,21 @@ def test_divergence_noalloc_argument_errors(L):
     assert re.search(r"#define\s+COMBO_DIVERGENCE_NOALLOC_MAX_WORKERS\s+128\b", header)
 
 
+def test_bandwidth_probe_argument_errors(L):
+    f = L.combo_bandwidth_probe
+    f.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64,
+                  ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
+    assert f(-1, FAKE_A, FAKE_B, 4, 1024, 1000, 0, 1, None) == EINVAL        # unknown kind
+    assert f(6, FAKE_A, FAKE_B, 4, 1024, 1000, 0, 1, None) == EINVAL
+    assert f(0, None, FAKE_B, 4, 1024, 1000, 0, 1, None) == EINVAL
+    assert f(0, FAKE_A, None, 4, 1024, 1000, 0, 1, None) == EINVAL           # only the write probe needs no source
+    assert f(0, FAKE_A, FAKE_B, 4, 999, 1000, 0, 1, None) == EINVAL          # ld < P
+    assert f(0, FAKE_A, FAKE_B, 4, 1001, 1000, 0, 1, None) == EINVAL         # pitch not a multiple of 4
+    assert f(0, ctypes.c_void_p(0x10000004), FAKE_B, 4, 1024, 1000, 0, 1, None) == EINVAL
+    assert f(0, FAKE_A, FAKE_A, 4, 1024, 1000, 0, 1, None) == EALIAS
+    assert f(0, FAKE_A, FAKE_B, 4, 1 << 61, 1000, 0, 1, None) == ERANGE
+
+
 def test_hashed_round_argument_errors(L):
     f = L.combo_round_hashed
 
