@@ -52,7 +52,8 @@ def test_committed_counter_profiles_match_the_kernel_sources():
     sys.path.insert(0, ROOT)
     import bench
     for wl, layout in (("c5_bertlarge", "tiled"), ("c5_bertlarge", "rows"), ("c2_resnet18", "tiled"),
-                       ("c2_resnet18", "rows"), ("c3_resnet50", "tiled"), ("c4_prime_fused", "tiled")):
+                       ("c2_resnet18", "rows"), ("c3_resnet50", "tiled"), ("c3_resnet50", "rows"),
+                       ("c4_prime_fused", "tiled"), ("c4_prime_fused", "rows")):
         nbytes, source = bench.recorded_traffic(wl, layout)
         assert nbytes is not None and os.path.exists(os.path.join(ROOT, source)), (wl, layout)
         from paper_1908_07782_amd.workloads import WORKLOADS
