@@ -564,6 +564,7 @@ def measure(combo, wl, args, layout, steps, warmup, trials, with_oracle, cpu_bud
     res["hbm_gbs"] = (traffic or hbm_bytes) / (kern_avg_ms * 1e-3) / 1e9
     res["hbm_frac"] = res["hbm_gbs"] / HBM_PEAK_GBS
     res["effective_gbs"] = alg_bytes / (kern_avg_ms * 1e-3) / 1e9
+    res["effective_pct_of_hbm_peak"] = 100.0 * res["effective_gbs"] / HBM_PEAK_GBS   # LDS reuse: may exceed 100
     res["bandwidth_meaningful"] = 8 * N * P > 512 * 1024 * 1024   # below: the arena sits in cache
     return res
 
