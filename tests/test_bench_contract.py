@@ -40,6 +40,10 @@ def test_bench_prints_one_json_line_with_the_required_fields():
     assert r["algorithmic_bytes_per_launch"] == 4 * (2 + 2) * 4 * 65536
     p = d["parity"]
     assert p["ok"] and p["tables_bit_exact"] and p["max_rel_err"] <= 1e-6
+    # against the binary64 oracle: R adds and one scale, each within 2^-24 relative, on sums of
+    # R+1 values; max|x| / max|result| stays below 8 for the workloads' distributions
+    n64 = p["normwise_err_vs_f64_oracle"]
+    assert n64 is None or 0 < n64 <= 8 * (8 + 3) * 2.0 ** -24
     assert p["columns_checked"] == p["of_columns"] == 65536
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["cores"] == 1 and c["value"] > 0 and c["sample"] and c["cpu_model"]
