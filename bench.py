@@ -159,6 +159,12 @@ def extras(combo, wl):
                 lambda: combo.bandwidth_probe(kind, arena[1], None if kind == combo.PROBE_WRITE else arena[0], P,
                                               cols=run << 4, param=flight, stream=stream), stream), nbytes,
                 note="bytes as for the plain probe")
+            if kind != combo.PROBE_READ and flight == 1:
+                emit(f"probe: {what}, 1 word in flight, XCD runs of {run} blocks, stores written through to "
+                     "device scope", time_kernel(
+                    lambda: combo.bandwidth_probe(kind, arena[1], None if kind == combo.PROBE_WRITE else arena[0], P,
+                                                  cols=(run << 4) | 2, param=flight, stream=stream), stream), nbytes,
+                    note="bytes as for the plain probe")
     for flight in (1, 2, 4, 8):
         emit(f"probe: read only, {flight} words in flight", time_kernel(
             lambda: combo.bandwidth_probe(combo.PROBE_READ, arena[1], arena[0], P, param=flight, stream=stream),

@@ -346,9 +346,11 @@ int combo_aggregation_divergence_noalloc(double* d_dist2, const float* d_x, int6
  *   COMBO_PROBE_COPY        flat copy of the N*ld floats, 128-bit streaming loads and stores;
  *                           param = words in flight per thread (1, 2, 4, 8); cols bit 0 = 0:
  *                           the words of a thread are 4 KiB apart, 1: the words of one
- *                           wavefront are consecutive KiB; cols >> 4 = k != 0: the XCDs take
- *                           turns at runs of k consecutive workgroup blocks, as the slab
- *                           kernel's strip order does (also for the next two)
+ *                           wavefront are consecutive KiB; cols bit 1: the stores are written
+ *                           through to device scope instead of carrying the non-temporal
+ *                           hint; cols >> 4 = k != 0: the XCDs take turns at runs of k
+ *                           consecutive workgroup blocks, as the slab kernel's strip order
+ *                           does (the last two also for the next two kinds)
  *   COMBO_PROBE_READ        the same loads folded to one float per workgroup, written to
  *                           d_dst[workgroup] (d_dst needs N*ld / (1024*param) + 1 floats)
  *   COMBO_PROBE_WRITE       the same stores of a constant; d_src may be NULL

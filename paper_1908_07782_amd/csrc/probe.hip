@@ -38,10 +38,19 @@ __device__ __forceinline__ uint64_t probe_word(int u, uint32_t run) {
     return base + (uint64_t)u * kProbeThreads + threadIdx.x;
 }
 
+// A 128-bit store with the hint the aggregation kernels use (non-temporal), or, `through` set,
+// one that is written through to device scope (the sc1 bit) instead of waiting in the L2 for
+// its eviction.  Plain copies run about 3.5 % faster with the latter; the aggregation kernels do
+// not (their stores come in bursts of a whole slab, which the write-back L2 absorbs).
+__device__ __forceinline__ void probe_store(v4f* p, v4f v, uint32_t through) {
+    if (through) asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+    else __builtin_nontemporal_store(v, p);
+}
+
 template <int FLIGHT, bool ADJACENT>
 __global__ __launch_bounds__(kProbeThreads) void probe_copy_kernel(float* __restrict__ dst,
                                                                    const float* __restrict__ src,
-                                                                   uint64_t n4, uint32_t run) {
+                                                                   uint64_t n4, uint32_t run, uint32_t through) {
     v4f v[FLIGHT];
 #pragma unroll
     for (int u = 0; u < FLIGHT; ++u) {
@@ -51,7 +60,7 @@ __global__ __launch_bounds__(kProbeThreads) void probe_copy_kernel(float* __rest
 #pragma unroll
     for (int u = 0; u < FLIGHT; ++u) {
         const uint64_t i = probe_word<FLIGHT, ADJACENT>(u, run);
-        if (i < n4) __builtin_nontemporal_store(v[u], reinterpret_cast<v4f*>(dst) + i);
+        if (i < n4) probe_store(reinterpret_cast<v4f*>(dst) + i, v[u], through);
     }
 }
 
@@ -81,12 +90,13 @@ __global__ __launch_bounds__(kProbeThreads) void probe_read_kernel(float* __rest
 }
 
 template <int FLIGHT, bool ADJACENT>
-__global__ __launch_bounds__(kProbeThreads) void probe_write_kernel(float* __restrict__ dst, uint64_t n4, uint32_t run) {
+__global__ __launch_bounds__(kProbeThreads) void probe_write_kernel(float* __restrict__ dst, uint64_t n4, uint32_t run,
+                                                                    uint32_t through) {
     const v4f c = v4f{1.0f, 2.0f, 3.0f, 4.0f};
 #pragma unroll
     for (int u = 0; u < FLIGHT; ++u) {
         const uint64_t i = probe_word<FLIGHT, ADJACENT>(u, run);
-        if (i < n4) __builtin_nontemporal_store(c, reinterpret_cast<v4f*>(dst) + i);
+        if (i < n4) probe_store(reinterpret_cast<v4f*>(dst) + i, c, through);
     }
 }
 
@@ -140,8 +150,8 @@ __global__ __launch_bounds__(kProbeThreads) void probe_multi_read_kernel(float* 
 }  // namespace
 
 // kind: 0 linear copy, 1 read only, 2 write only (n = N*ld floats, `param` = 128-bit words in
-// flight per thread: 1, 2, 4 or 8; cols bit 0: the words of a wavefront are adjacent; cols >> 4:
-// blocks per XCD turn); 3 row-chunk copy, 4 tile copy (`cols` columns per strip);
+// flight per thread: 1, 2, 4 or 8; cols bit 0: the words of a wavefront are adjacent; cols bit 1:
+// stores written through to device scope; cols >> 4: blocks per XCD turn); 3 row-chunk copy, 4 tile copy (`cols` columns per strip);
 // 5 multi-read pass (`param` = rows read per output).  Only whole 128-bit words, strips and
 // tiles are touched.  Returns hipErrorInvalidValue for shapes the probes do not cover.
 hipError_t launch_bandwidth_probe(int kind, float* dst, const float* src, int32_t N, int64_t ld, int64_t P,
@@ -152,6 +162,7 @@ hipError_t launch_bandwidth_probe(int kind, float* dst, const float* src, int32_
         const uint64_t per_wg = (uint64_t)kProbeThreads * (uint64_t)param;
         uint64_t grid64 = (n4 + per_wg - 1) / per_wg;
         const bool adjacent = (cols & 1) != 0;
+        const uint32_t through = (cols & 2) != 0 ? 1u : 0u;
         const uint32_t run = (uint32_t)(cols >> 4);              // blocks per XCD turn, 0: block = id
         if (run != 0) grid64 = (grid64 + 8ull * run - 1) / (8ull * run) * (8ull * run);   // surplus blocks are out of range
         // a grid dimension holds fewer than 2^32 work-items
@@ -167,9 +178,9 @@ hipError_t launch_bandwidth_probe(int kind, float* dst, const float* src, int32_
             case 16: hipLaunchKernelGGL((KERNEL<8, false>), grid, block, 0, st, __VA_ARGS__); break;      \
             default: hipLaunchKernelGGL((KERNEL<8, true>), grid, block, 0, st, __VA_ARGS__); break;       \
         }
-        if (kind == 0) { COMBO_PROBE_FLIGHT(probe_copy_kernel, dst, src, n4, run) }
+        if (kind == 0) { COMBO_PROBE_FLIGHT(probe_copy_kernel, dst, src, n4, run, through) }
         else if (kind == 1) { COMBO_PROBE_FLIGHT(probe_read_kernel, dst, src, n4, run) }
-        else { COMBO_PROBE_FLIGHT(probe_write_kernel, dst, n4, run) }
+        else { COMBO_PROBE_FLIGHT(probe_write_kernel, dst, n4, run, through) }
 #undef COMBO_PROBE_FLIGHT
         return hipGetLastError();
     }
