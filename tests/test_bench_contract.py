@@ -47,6 +47,8 @@ def test_bench_prints_one_json_line_with_the_required_fields():
     assert p["columns_checked"] == p["of_columns"] == 65536
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["cores"] == 1 and c["value"] > 0 and c["sample"] and c["cpu_model"]
+    # beside the single-thread figure of record: the same library from parallel threads
+    assert c["all_cores"]["value"] > 0 and c["all_cores"]["equals_single_call_on_sampled_windows"]
 
 
 def test_committed_counter_profiles_match_the_kernel_sources():
