@@ -126,3 +126,134 @@ def test_c5_bertlarge_all_rounds_on_offset_crossings_and_random_windows(combo, r
         want = tp.oracle_rounds_on_window(ref, wl, X0[:, at:at + n], c0, wl.rounds)
         assert np.array_equal(bits(got[:, at:at + n]), bits(want)), (layout, c0, n)
         at += n
+
+
+# --- properties that hold at any size, checked on every element of the c5 arena in the launch
+# --- configuration the benchmark times.  The inputs and the views of the tiled arena are made
+# --- with torch alone (no pack / unpack kernel of the library is involved).
+
+def c5_arena(combo, layout, fill_row):
+    """(input half, NaN-filled output half, row view function, Wt) of a c5-sized arena whose
+    row w is fill_row(w) (a 1-D tensor of P floats or a scalar)."""
+    wl = combo.workloads.WORKLOADS["c5_bertlarge"]
+    N, P, R = wl.N, wl.P, wl.R
+    if layout == "rows":
+        arena = torch.empty((2, N, wl.ld), dtype=torch.float32, device="cuda")
+        arena[0].fill_(float("nan"))
+        for w in range(N):
+            arena[0][w, :P] = fill_row(w)
+        arena[1].fill_(float("nan"))
+        return arena, (lambda buf, w: buf[w, :P]), 0
+    Wt = combo.tiled_cols(N, R)
+    T = -(-P // Wt)
+    arena = torch.empty((2, T * N * Wt), dtype=torch.float32, device="cuda")
+    v = arena[0].view(T, N, Wt)
+    for w in range(N):
+        r = fill_row(w)
+        if torch.is_tensor(r):
+            padded = torch.full((T * Wt,), float("nan"), dtype=torch.float32, device="cuda")
+            padded[:P] = r
+            v[:, w, :] = padded.view(T, Wt)
+            del padded
+        else:
+            v[:, w, :] = r
+    arena[1].fill_(float("nan"))
+    return arena, (lambda buf, w: buf.view(T, N, Wt)[:, w, :].reshape(-1)[:P]), Wt
+
+
+def c5_round(combo, arena, Wt, peers, R=None):
+    wl = combo.workloads.WORKLOADS["c5_bertlarge"]
+    R = wl.R if R is None else R
+    if Wt == 0:
+        combo.segment_gossip_round(arena[1], arena[0], peers, wl.P, wl.S, R)
+    else:
+        combo.segment_gossip_round_tiled(arena[1], arena[0], Wt, peers, wl.N, wl.P, wl.S, R)
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("layout", ["rows", "tiled"])
+def test_c5_constant_rows_pin_every_element_to_its_segment_and_peers(combo, ref, layout):
+    """Row w holds one value c_w everywhere.  Then every element of segment s of worker w must be
+    the one number ((c_w + c_p0) + c_p1 ...) * fl(1/(R+1)) that the table fixes (Eq. 3), so a
+    single misplaced segment boundary or peer index anywhere in the 5.4e9 elements shows."""
+    wl = combo.workloads.WORKLOADS["c5_bertlarge"]
+    N, P, S, R = wl.N, wl.P, wl.S, wl.R
+    c = np.random.default_rng(77).standard_normal(N).astype(np.float32)
+    arena, row_of, Wt = c5_arena(combo, layout, lambda w: float(c[w]))
+    table = ref.make_peer_table(N, S, R, wl.hash_seed, 3)            # (N, S, R)
+    peers = torch.from_numpy(np.ascontiguousarray(table).reshape(-1)).cuda()
+    c5_round(combo, arena, Wt, peers)
+    inv = np.float32(1.0) / np.float32(R + 1)
+    L = P // S
+    for w in range(N):
+        row = row_of(arena[1], w).contiguous().view(torch.int32)
+        for s in range(S):
+            acc = c[w]
+            for j in range(R):
+                acc = np.float32(acc + c[table[w, s, j]])
+            want = int(np.float32(acc * inv).view(np.int32))
+            lo, hi = s * L, (P if s == S - 1 else (s + 1) * L)
+            assert bool((row[lo:hi] == want).all()), (layout, w, s)
+        del row
+
+
+@pytest.mark.parametrize("layout", ["rows", "tiled"])
+def test_c5_identical_workers_stay_identical(combo, layout):
+    """All workers start from one model (Sec. 4.1 initialisation): after a round all rows are
+    bitwise equal to each other, and equal to the input within 2 ulp."""
+    wl = combo.workloads.WORKLOADS["c5_bertlarge"]
+    N, P, S, R = wl.N, wl.P, wl.S, wl.R
+    g = torch.Generator(device="cuda").manual_seed(11)
+    x = torch.empty(P, dtype=torch.float32, device="cuda").normal_(0, 0.02, generator=g)
+    arena, row_of, Wt = c5_arena(combo, layout, lambda w: x)
+    peers = torch.empty(N * S * R, dtype=torch.int32, device="cuda")
+    combo.make_peer_table(peers, N, S, R, wl.hash_seed, 1)
+    c5_round(combo, arena, Wt, peers)
+    first = row_of(arena[1], 0).contiguous()
+    assert bool(((first - x).abs() <= 2.5e-7 * x.abs()).all())
+    for w in range(1, N):
+        assert torch.equal(row_of(arena[1], w).contiguous().view(torch.int32), first.view(torch.int32)), (layout, w)
+
+
+@pytest.mark.parametrize("layout", ["rows", "tiled"])
+def test_c5_size_all_peers_is_the_global_average(combo, layout):
+    """R = N-1 (every other worker is pulled): each row is the column mean (the FedAvg limit of
+    Sec. 4.3) up to the rounding of N-1 fp32 adds and one scale."""
+    wl = combo.workloads.WORKLOADS["c5_bertlarge"]
+    N, P, S = wl.N, wl.P, wl.S
+    R = N - 1
+
+    def fill(w):
+        g = torch.Generator(device="cuda").manual_seed(100 + w)
+        return torch.empty(P, dtype=torch.float32, device="cuda").normal_(0, 0.02, generator=g)
+
+    wl_cols = combo.tiled_cols(N, R)
+    if layout == "rows":
+        arena, row_of, Wt = c5_arena(combo, "rows", fill)
+    else:
+        # the tile width follows R: build the arena for it
+        T = -(-P // wl_cols)
+        arena = torch.empty((2, T * N * wl_cols), dtype=torch.float32, device="cuda")
+        v = arena[0].view(T, N, wl_cols)
+        for w in range(N):
+            padded = torch.full((T * wl_cols,), float("nan"), dtype=torch.float32, device="cuda")
+            padded[:P] = fill(w)
+            v[:, w, :] = padded.view(T, wl_cols)
+            del padded
+        arena[1].fill_(float("nan"))
+        Wt = wl_cols
+        row_of = lambda buf, w: buf.view(T, N, Wt)[:, w, :].reshape(-1)[:P]      # noqa: E731
+    peers = torch.empty(N * S * R, dtype=torch.int32, device="cuda")
+    combo.make_peer_table(peers, N, S, R, wl.hash_seed, 2)
+    c5_round(combo, arena, Wt, peers, R=R)
+    mean = torch.zeros(P, dtype=torch.float64, device="cuda")
+    biggest = 0.0
+    for w in range(N):
+        r = row_of(arena[0], w)
+        mean += r.double()
+        biggest = max(biggest, float(r.abs().max()))
+    mean /= N
+    bound = (N + 1) * 2.0 ** -24 * biggest
+    for w in range(N):
+        err = float((row_of(arena[1], w).double() - mean).abs().max())
+        assert err <= bound, (layout, w, err, bound)
