@@ -247,6 +247,7 @@ struct TileDivArgs {
     int32_t N;
     int32_t Wt;           // tile width: 64, 128 or 256
     uint64_t ntiles;
+    uint32_t run;         // the XCDs take turns at runs of `run` consecutive workgroup positions (0: none)
 };
 
 // U tiles per pass of a wavefront, kDivSlots / U register slots for the rows of each.
@@ -283,7 +284,7 @@ __global__ __launch_bounds__(256) void divergence_tile_kernel(const TileDivArgs 
     }
 
     const uint64_t nwaves = (uint64_t)gridDim.x * 4u;
-    for (uint64_t first = ((uint64_t)blockIdx.x * 4u + (uint64_t)wave) * U; first < a.ntiles;
+    for (uint64_t first = ((uint64_t)xcd_run_block(blockIdx.x, a.run) * 4u + (uint64_t)wave) * U; first < a.ntiles;
          first += nwaves * U) {
         v4f v[kDivSlots];
 #pragma unroll
@@ -424,7 +425,11 @@ hipError_t launch_divergence(double* dist2, double* workspace, const float* x, i
     if (strips > 0xFFFFFFFFull) return hipErrorInvalidValue;
     const int threads = divergence_threads(N, W);
     const size_t lds = divergence_lds_bytes(N, W, threads);
-    // persistent grid: exactly the workgroups that are resident at once (no tail round)
+    // persistent grid: workgroups that are resident at once (no tail round), but no more than
+    // three per compute unit for 256-thread workgroups: each keeps 32 KiB of loads in flight, and
+    // beyond about 96 KiB per compute unit the memory system delivers less, not more (MI355X,
+    // row-major arenas: c2 6.37 against 6.15 TB/s with all five resident, c3 6.74 / 6.33,
+    // c5 6.71 / 6.44, c4 5.5 / 5.1; two per compute unit are slower again)
     static int resident[2][2] = {{0, 0}, {0, 0}};   // [weighted][512 threads]
     int& res = resident[dsz != nullptr][threads == 512];
     if (res == 0) {
@@ -441,6 +446,7 @@ hipError_t launch_divergence(double* dist2, double* workspace, const float* x, i
         if (qe != hipSuccess || hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
             return hipErrorUnknown;
+        if (threads == 256 && per_cu > 3) per_cu = 3;
         res = per_cu * cus;
         if (res < 1) res = 256;
         if (res > kDivPartialsPerRow) res = kDivPartialsPerRow;   // the workspace's partials per row
@@ -511,7 +517,10 @@ hipError_t launch_divergence_tiles(double* dist2, double* workspace, const float
     const int U = tiles_per_pass(N, tile_cols);
     const TileDivKernel kernel = tile_kernel_for(dsz != nullptr, U);
     const size_t lds = (size_t)256 * 8 + (size_t)N * 4;
-    // persistent grid: the workgroups that are resident at once
+    // persistent grid: two workgroups per compute unit (eight wavefronts with 8 KiB of loads in
+    // flight each; with all four that fit, the memory system delivers 3-4 % less: c5 6.79 against
+    // 7.09 TB/s, c3 6.64 / 6.95, c2 6.45 / 6.70), the XCDs taking turns at runs of four
+    // workgroup positions (128 KiB of consecutive tiles per pass; worth 1 % of that)
     static int resident[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}};   // [weighted][log2 U]
     int& res = resident[dsz != nullptr][U == 8 ? 3 : U == 4 ? 2 : U == 2 ? 1 : 0];
     if (res == 0) {
@@ -520,6 +529,7 @@ hipError_t launch_divergence_tiles(double* dist2, double* workspace, const float
             hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
             return hipErrorUnknown;
+        if (per_cu > 2) per_cu = 2;
         res = per_cu * cus;
         if (res < 1) res = 256;
         if (res > kDivPartialsPerRow) res = kDivPartialsPerRow;   // the workspace's partials per row
@@ -534,6 +544,8 @@ hipError_t launch_divergence_tiles(double* dist2, double* workspace, const float
     a.ntiles = ((uint64_t)P + (uint64_t)tile_cols - 1) / (uint64_t)tile_cols;
     const uint64_t passes = (a.ntiles + (uint64_t)(4 * U) - 1) / (uint64_t)(4 * U);   // per workgroup of 4 wavefronts
     const uint32_t grid = (uint32_t)(passes < (uint64_t)res ? passes : (uint64_t)res);
+    // the run order permutes the positions [0, grid) only if grid is a whole number of rounds of 8 runs
+    a.run = grid % (kXcds * 4u) == 0 ? 4u : 0u;
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), lds, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
