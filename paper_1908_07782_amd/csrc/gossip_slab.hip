@@ -31,7 +31,14 @@ int slab_threads(int32_t N, int W) {
 // does not hold where a workgroup spends longer between its loads and its stores: with
 // dataset-size weights or dynamic workers the two extra workgroups are worth 8-10 % (c2
 // weighted: 0.49 vs 0.55 ms), from R = 8 on 2-5 %, and on the largest arena 1 %.  512-thread
-// workgroups are four per compute unit anyway.  The knob: 0 = this rule, else the floor in bytes.
+// workgroups are four per compute unit anyway.
+// With fused local steps a workgroup has the gradient slab in flight as well (and with more than
+// one step the next slice on top), and what the memory system takes best is 64-80 KiB of loads
+// per compute unit, as for every streaming kernel here: four resident workgroups (36 KiB each)
+// for one step, three (44 KiB) for more (c5 with a step: 6.64 against 6.42 TB/s of 12 B per
+// element; two steps: 6.41 against 6.15 of 16 B; c2 with two steps 6.50 against 6.20; like the
+// rule above only while the aggregation is short: 32 workers with R = 8 lose 5 % that way).
+// The knob: 0 = this rule, else the floor in bytes.
 std::atomic<int> g_slab_lds_floor{0};
 void set_slab_lds_floor(int bytes) { g_slab_lds_floor.store(bytes); }
 int get_slab_lds_floor() { return g_slab_lds_floor.load(); }
@@ -40,8 +47,10 @@ size_t slab_lds_request(const RoundArgs& a, int W, bool hashed) {
     size_t floor_bytes = (size_t)g_slab_lds_floor.load();
     const bool short_aggregation = a.R <= 4 && a.dsz == nullptr && a.status == nullptr;
     const bool small_arena = (uint64_t)a.N * (uint64_t)a.P * sizeof(float) < (7ull << 30);
-    if (floor_bytes == 0 && slab_threads(a.N, W) == 256 && short_aggregation && small_arena)
-        floor_bytes = 24 * 1024;
+    if (floor_bytes == 0 && slab_threads(a.N, W) == 256 && short_aggregation) {
+        if (a.grad != nullptr) floor_bytes = (a.tau >= 2 ? 44 : 36) * 1024;
+        else if (small_arena) floor_bytes = 24 * 1024;
+    }
     return used > floor_bytes ? used : floor_bytes;
 }
 
