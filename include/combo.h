@@ -206,10 +206,12 @@ int combo_segment_gossip_round_dynamic(float* d_dst, const float* d_src, int64_t
  * padding: never read, never written.  Element-wise work (the local SGD step) is
  * layout-agnostic, so a simulation can live in this layout and unpack only to export.
  *
- *   combo_tiled_cols(N, R)          recommended Wt (a power of two in [8, 1024]: 8 KiB tiles
- *                                   for N <= 32 - 32 KiB ones for R > 8, where more data in
- *                                   flight hides the longer aggregation -, then the widest
- *                                   of 64, 32, 16, 8 columns whose tile stays within 32 KiB),
+ *   combo_tiled_cols(N, R)          recommended Wt (a power of two in [8, 1024]: for N <= 32
+ *                                   the narrowest one whose tile reaches 8 KiB, i.e. tiles of
+ *                                   8 KiB to just under 16 KiB - for R > 8 the widest within
+ *                                   32 KiB, where more data in flight hides the longer
+ *                                   aggregation -, then the widest of 64, 32, 16, 8 columns
+ *                                   whose tile stays within 32 KiB),
  *                                   or a negative status if N rows of 8 columns do not fit in
  *                                   LDS (N*(44 + 4*R) > 65536)
  *   combo_tiled_elems(N, P, Wt)     floats in one tiled matrix, = T*N*Wt

@@ -345,14 +345,25 @@ int64_t combo_tiled_elems(int32_t N, int64_t P, int32_t tile_cols) {
 
 int32_t combo_tiled_cols(int32_t N, int32_t R) {
     if (N < 1 || R < 0) return COMBO_EINVAL;
-    // 8 KiB slabs measured best while a row chunk has at least 64 columns (N <= 32), 32 KiB
-    // ones for more than 8 replicas; for more workers keep the chunk as wide as a slab of at
-    // most 32 KiB allows (64 columns up to N = 128, 32 up to 256, 16 up to 512, then 8): a
-    // tile is one contiguous block whatever its width, so narrow tiles keep many-worker
-    // arenas on the LDS-slab kernel
+    // Up to 8 replicas: the narrowest power of two (from 64 columns) whose tile reaches 8 KiB, so
+    // tiles of 8 KiB to just under 16 KiB for N <= 32.  Measured on MI355X: 8 KiB where N is a
+    // power of two; for other N the next width down leaves 4-8 KiB tiles, which are 2-18 % slower
+    // than the 8-16 KiB ones (20 workers: 5 KiB 5.2 TB/s, 10 KiB 6.1; 30 workers: 7.5 KiB 6.14,
+    // 15 KiB 6.26; 12 workers: 6 KiB 5.85, 12 KiB 6.17).  More than 8 replicas: the widest tile
+    // within 32 KiB.  For more workers keep the chunk as wide as a slab of at most 32 KiB allows
+    // (64 columns up to N = 128, 32 up to 256, 16 up to 512, then 8): a tile is one contiguous
+    // block whatever its width, so narrow tiles keep many-worker arenas on the LDS-slab kernel
     const int64_t budget = (int64_t)combo::slab_budget_bytes(R, true);
-    for (int W = 1024; W >= 64; W >>= 1)
-        if ((int64_t)N * W * 4 <= budget && combo::slab_strip_cols(N, R, W) == W) return W;
+    if (R <= 8) {
+        for (int W = 64; W <= 1024; W <<= 1) {
+            const int64_t bytes = (int64_t)N * W * 4;
+            if ((bytes >= budget || W == 1024) && bytes <= 32 * 1024 && combo::slab_strip_cols(N, R, W) == W)
+                return W;
+        }
+    } else {
+        for (int W = 1024; W >= 64; W >>= 1)
+            if ((int64_t)N * W * 4 <= budget && combo::slab_strip_cols(N, R, W) == W) return W;
+    }
     for (int W = 64; W >= 8; W >>= 1)
         if ((int64_t)N * W * 4 <= 32 * 1024 && combo::slab_strip_cols(N, R, W) == W) return W;
     return combo::slab_strip_cols(N, R, 8) == 8 ? 8 : COMBO_ERANGE;

@@ -234,8 +234,12 @@ def test_tiled_layout_sizes_and_recommended_widths(L):
     tiled matrix has."""
     cols, elems = L.combo_tiled_cols, L.combo_tiled_elems
     assert cols(0, 1) == EINVAL and cols(4, -1) == EINVAL
-    # 8 KiB tiles while a row chunk keeps at least 64 columns
+    # the narrowest width whose tile reaches 8 KiB: 8 KiB for powers of two, up to 16 KiB between
     assert [cols(n, 4) for n in (4, 8, 16, 32)] == [512, 256, 128, 64] and cols(2, 1) == 1024
+    assert [cols(n, 2) for n in (3, 5, 10, 12, 20, 24, 30)] == [1024, 512, 256, 256, 128, 128, 128]
+    assert cols(1, 0) == 1024
+    # more than 8 replicas: the widest tile within 32 KiB
+    assert [cols(n, 12) for n in (16, 20, 30, 32, 40, 64)] == [512, 256, 256, 256, 128, 128]
     # then the widest of 64, 32, 16, 8 columns whose tile stays within 32 KiB
     assert [cols(n, 3) for n in (33, 100, 128, 129, 256, 257, 512, 513, 1000)] == \
         [64, 64, 64, 32, 32, 16, 16, 8, 8]
