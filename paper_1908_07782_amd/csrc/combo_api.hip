@@ -145,14 +145,19 @@ int enqueue_round(float* dst, const float* src, const float* grad, float lr, int
         // tried from 6 to 21 GiB (c5 6.31 -> 6.43, 100 x 30 M 5.86 -> 6.27 TB/s); runs of 4 or
         // 8 tiles are 5-10 % slower than strip = id, runs that are not powers of two lose
         // 2-4 %, whole eighths lose 2-10 % on small arenas.  Rounds that change layout gain
-        // too when one side is tiled (c2: +3-5 %).  Row-major arenas keep strip = id: runs of
-        // 4-8 strips gain 3-4 % on c2 and c3 but lose 3-6 % on c5, and longer runs lose
-        // everywhere (the L2 -> fabric request stalls double).
+        // too when one side is tiled (c2: +3-5 %).  Row-major arenas: what counts is how many
+        // consecutive bytes of a row one XCD takes at a time, and 2 KiB is the best (measured over
+        // three placements of each arena, both directions): strips of 128 columns in runs of 4
+        // (c2 +1.5 %, c3 +3 %, 20 and 30 workers +2.4 %), strips of 64 columns in runs of 8 (64
+        // workers +6 %, c4 +1 %), strips of 256 columns and more as they come (c5: runs of 4 lose
+        // 2.4 %); runs that are not powers of two and longer runs lose everywhere (the L2 ->
+        // fabric request stalls double).
         const int order = g_slab_order.load();
         const bool any_tiled = a.tile_shift != 0 || a.dst_tile_shift != 0;
         if (order == 2) a.strips_per_xcd = (a.nstrips + combo::kXcds - 1) / combo::kXcds;
         else if (order >= 3) a.strips_per_xcd = (uint32_t)order;   // runs of this many strips
         else if (order == 0 && any_tiled) a.strips_per_xcd = tile_run(N, P);
+        else if (order == 0 && plan.cols <= 128) a.strips_per_xcd = (uint32_t)(512 / plan.cols);
         if (combo::slab_grid(a, plan.cols) == 0) return COMBO_ERANGE;   // work-items per grid dimension
     }
     a.hash_sr = hash_sr;
