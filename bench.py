@@ -182,6 +182,18 @@ def extras(combo, wl):
         emit(f"probe: tile copy, one contiguous N x {cols} tile per workgroup (tiled footprint)",
              time_kernel(lambda: combo.bandwidth_probe(combo.PROBE_TILES, arena[1], arena[0], P, cols=cols,
                                                        stream=stream), stream), moved, note="bytes = read + write")
+        if cols <= 128:
+            # the same copies with the strip orders the round uses: 2 KiB of consecutive columns of a row
+            # per XCD turn on the row-major arena, runs of 16 tiles on the tiled one
+            run = 512 // cols
+            emit(f"probe: row-chunk copy, N chunks of {cols} columns per workgroup, XCD runs of {run} strips",
+                 time_kernel(lambda: combo.bandwidth_probe(combo.PROBE_ROW_CHUNKS, arena[1], arena[0], P, cols=cols,
+                                                           param=run, stream=stream), stream), moved,
+                 note="bytes = read + write")
+            emit(f"probe: tile copy, one contiguous N x {cols} tile per workgroup, XCD runs of 16 tiles",
+                 time_kernel(lambda: combo.bandwidth_probe(combo.PROBE_TILES, arena[1], arena[0], P, cols=cols,
+                                                           param=16, stream=stream), stream), moved,
+                 note="bytes = read + write")
     for k in sorted({1, 3, R + 1}):
         emit(f"probe: {k} read streams + 1 write stream, no reuse out of LDS (worker-major order)",
              time_kernel(lambda: combo.bandwidth_probe(combo.PROBE_MULTI_READ, arena[1], arena[0], P, param=k,

@@ -357,7 +357,9 @@ int combo_aggregation_divergence_noalloc(double* d_dist2, const float* d_x, int6
  *                           d_dst[workgroup] (d_dst needs N*ld / (1024*param) + 1 floats)
  *   COMBO_PROBE_WRITE       the same stores of a constant; d_src may be NULL
  *   COMBO_PROBE_ROW_CHUNKS  per workgroup N row chunks of `cols` columns, rows ld apart: the
- *                           slab kernel's footprint on a row-major arena (no LDS, no gather)
+ *                           slab kernel's footprint on a row-major arena (no LDS, no gather);
+ *                           param > 1: the XCDs take turns at runs of `param` consecutive
+ *                           strips (also for the next kind), else strip i to workgroup i
  *   COMBO_PROBE_TILES       per workgroup one contiguous N x cols tile: the footprint on a
  *                           tiled arena; the first (P / cols)*N*cols floats are copied
  *   COMBO_PROBE_MULTI_READ  d_dst[w][e] = sum of `param` rows w, w+1, ... (wrapping) of

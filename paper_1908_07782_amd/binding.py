@@ -472,9 +472,12 @@ def round_relayout(dst, dst_tile_cols, src, src_tile_cols, peers, N, P, S, R, *,
 PROBE_COPY, PROBE_READ, PROBE_WRITE, PROBE_ROW_CHUNKS, PROBE_TILES, PROBE_MULTI_READ = range(6)
 
 
-def bandwidth_probe(kind, dst, src, P, cols=0, param=4, stream=None):
+def bandwidth_probe(kind, dst, src, P, cols=0, param=None, stream=None):
     """combo_bandwidth_probe on (N, ld) float32 device matrices (src may be None for the
-    write-only probe)."""
+    write-only probe).  param defaults to 4 words in flight for the flat passes and to
+    strip i -> workgroup i for the strip copies."""
+    if param is None:
+        param = 0 if kind in (PROBE_ROW_CHUNKS, PROBE_TILES) else 4
     N = dst.shape[0]
     ld = _matrix(dst, "dst")
     if src is not None and (src.shape[0] != N or _matrix(src, "src") != ld):

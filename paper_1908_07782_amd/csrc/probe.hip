@@ -105,11 +105,14 @@ __global__ __launch_bounds__(kProbeThreads) void probe_write_kernel(float* __res
 template <bool TILED>
 __global__ __launch_bounds__(kProbeThreads) void probe_strip_copy_kernel(float* __restrict__ dst,
                                                                          const float* __restrict__ src,
-                                                                         int64_t ld, int32_t N, int cols) {
+                                                                         int64_t ld, int32_t N, int cols,
+                                                                         uint32_t nstrips, uint32_t run) {
+    const uint32_t strip = xcd_run_block(blockIdx.x, run);
+    if (strip >= nstrips) return;                  // surplus workgroup of the last round of runs
     const int W4 = cols >> 2;
     const int total4 = N * W4;
     const size_t stride = TILED ? (size_t)cols : (size_t)ld;
-    const size_t base = TILED ? (size_t)blockIdx.x * (size_t)N * (size_t)cols : (size_t)blockIdx.x * (size_t)cols;
+    const size_t base = TILED ? (size_t)strip * (size_t)N * (size_t)cols : (size_t)strip * (size_t)cols;
     for (int b = 0; b < total4; b += kProbeThreads * 4) {
         v4f v[4];
         size_t off[4];
@@ -151,7 +154,9 @@ __global__ __launch_bounds__(kProbeThreads) void probe_multi_read_kernel(float* 
 
 // kind: 0 linear copy, 1 read only, 2 write only (n = N*ld floats, `param` = 128-bit words in
 // flight per thread: 1, 2, 4 or 8; cols bit 0: the words of a wavefront are adjacent; cols bit 1:
-// stores written through to device scope; cols >> 4: blocks per XCD turn); 3 row-chunk copy, 4 tile copy (`cols` columns per strip);
+// stores written through to device scope; cols >> 4: blocks per XCD turn);
+// 3 row-chunk copy, 4 tile copy (`cols` columns per strip; `param` > 1: the XCDs take turns at
+// runs of `param` consecutive strips);
 // 5 multi-read pass (`param` = rows read per output).  Only whole 128-bit words, strips and
 // tiles are touched.  Returns hipErrorInvalidValue for shapes the probes do not cover.
 hipError_t launch_bandwidth_probe(int kind, float* dst, const float* src, int32_t N, int64_t ld, int64_t P,
@@ -187,13 +192,18 @@ hipError_t launch_bandwidth_probe(int kind, float* dst, const float* src, int32_
     if (kind == 3 || kind == 4) {
         if (cols < 4 || cols % 4 != 0 || P < cols) return hipErrorInvalidValue;
         const uint64_t strips = (uint64_t)P / (uint64_t)cols;        // whole strips only
-        if (strips > 0x7FFFFFFFull) return hipErrorInvalidValue;
+        if (param < 0 || param > 65536) return hipErrorInvalidValue;
+        const uint32_t run = param > 1 ? (uint32_t)param : 0u;
+        uint64_t grid64 = strips;
+        if (run != 0) grid64 = (strips + 8ull * run - 1) / (8ull * run) * (8ull * run);
+        // a grid dimension holds fewer than 2^32 work-items
+        if (strips > 0x7FFFFFF0ull || grid64 * kProbeThreads > 0xFFFFFFFFull) return hipErrorInvalidValue;
         if (kind == 3)
-            hipLaunchKernelGGL(probe_strip_copy_kernel<false>, dim3((uint32_t)strips), dim3(kProbeThreads), 0,
-                               st, dst, src, ld, N, cols);
+            hipLaunchKernelGGL(probe_strip_copy_kernel<false>, dim3((uint32_t)grid64), dim3(kProbeThreads), 0,
+                               st, dst, src, ld, N, cols, (uint32_t)strips, run);
         else
-            hipLaunchKernelGGL(probe_strip_copy_kernel<true>, dim3((uint32_t)strips), dim3(kProbeThreads), 0,
-                               st, dst, src, ld, N, cols);
+            hipLaunchKernelGGL(probe_strip_copy_kernel<true>, dim3((uint32_t)grid64), dim3(kProbeThreads), 0,
+                               st, dst, src, ld, N, cols, (uint32_t)strips, run);
         return hipGetLastError();
     }
     if (kind == 5) {

@@ -65,16 +65,18 @@ def test_strip_copies_touch_whole_strips_only(combo, N, P, ld, cols):
     src = torch.from_numpy(src_h).cuda()
     strips = P // cols
     dst = torch.full((N, ld), float("nan"), dtype=torch.float32, device="cuda")
-    combo.bandwidth_probe(combo.PROBE_ROW_CHUNKS, dst, src, P, cols=cols)
-    got = dst.cpu().numpy()
-    assert np.array_equal(bits(got[:, :strips * cols]), bits(src_h[:, :strips * cols]))
-    assert np.isnan(got[:, strips * cols:]).all()
-    dst.fill_(float("nan"))
-    combo.bandwidth_probe(combo.PROBE_TILES, dst, src, P, cols=cols)
-    got = dst.cpu().numpy().reshape(-1)
-    n = strips * N * cols
-    assert np.array_equal(bits(got[:n]), bits(src_h.reshape(-1)[:n]))
-    assert np.isnan(got[n:]).all()
+    for run in (0, 1, 4, 16):                      # strip i -> workgroup i, or XCD runs of `run` strips
+        dst.fill_(float("nan"))
+        combo.bandwidth_probe(combo.PROBE_ROW_CHUNKS, dst, src, P, cols=cols, param=run)
+        got = dst.cpu().numpy()
+        assert np.array_equal(bits(got[:, :strips * cols]), bits(src_h[:, :strips * cols])), run
+        assert np.isnan(got[:, strips * cols:]).all(), run
+        dst.fill_(float("nan"))
+        combo.bandwidth_probe(combo.PROBE_TILES, dst, src, P, cols=cols, param=run)
+        got = dst.cpu().numpy().reshape(-1)
+        n = strips * N * cols
+        assert np.array_equal(bits(got[:n]), bits(src_h.reshape(-1)[:n])), run
+        assert np.isnan(got[n:]).all(), run
 
 
 @pytest.mark.parametrize("N,P,ld", SHAPES)
