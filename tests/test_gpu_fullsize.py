@@ -6,7 +6,11 @@
     layouts, on windows placed where the flat element offset (and with it the byte offset)
     crosses 2^30, 2^31 and 2^32, plus a few hundred seeded random 64-column windows.  A
     round is column-separable (output column e depends on input column e only), so a
-    window of the full run equals the oracle's run on the window.
+    window of the full run equals the oracle's run on the window;
+  * properties that hold at any size on every element of the c5 arena (constant rows pinned
+    through the oracle's table, identical workers, all peers = column mean);
+  * the weighted round (Eq. 3 with dataset sizes) and the dynamic-worker round (Sec. 4.2) on
+    the whole c2 arena, both layouts.
 Everything is bitwise."""
 import numpy as np
 import pytest
@@ -257,3 +261,63 @@ def test_c5_size_all_peers_is_the_global_average(combo, layout):
     for w in range(N):
         err = float((row_of(arena[1], w).double() - mean).abs().max())
         assert err <= bound, (layout, w, err, bound)
+
+
+# --- the other variants of the round at a full configuration size (c2), every element
+
+def c2_run(combo, layout, rows, peers, *, dsz=None, status=None):
+    wl = combo.workloads.WORKLOADS["c2_resnet18"]
+    N, P, S, R = wl.N, wl.P, wl.S, wl.R
+    out = torch.full((N, wl.ld), float("nan"), dtype=torch.float32, device="cuda")
+    if layout == "rows":
+        if status is None:
+            combo.segment_gossip_round(out, rows, peers, P, S, R, dataset_sizes=dsz)
+        else:
+            combo.segment_gossip_round_dynamic(out, rows, peers, status, P, S, R, dataset_sizes=dsz)
+    else:
+        Wt = combo.tiled_cols(N, R)
+        t = torch.full((2, combo.tiled_elems(N, P, Wt)), float("nan"), dtype=torch.float32, device="cuda")
+        combo.pack_tiled(t[0], rows, N, P, Wt)
+        combo.segment_gossip_round_tiled(t[1], t[0], Wt, peers, N, P, S, R, dataset_sizes=dsz, status=status)
+        combo.unpack_tiled(out, t[1], N, P, Wt)
+    torch.cuda.synchronize()
+    return out
+
+
+@pytest.mark.parametrize("layout", ["rows", "tiled"])
+def test_c2_resnet18_full_weighted_round_elementwise(combo, ref, layout):
+    """Eq. (3) with dataset sizes on the whole c2 arena, bit for bit (the quotient included)."""
+    wl = combo.workloads.WORKLOADS["c2_resnet18"]
+    N, P, S, R = wl.N, wl.P, wl.S, wl.R
+    rows = torch.full((N, wl.ld), float("nan"), dtype=torch.float32, device="cuda")
+    combo.workloads.fill_params(rows, wl)
+    X0 = host_rows(rows, P)
+    d = (np.random.default_rng(21).integers(100, 5000, N)).astype(np.float32)
+    table = ref.make_peer_table(N, S, R, wl.hash_seed, 4)
+    peers = torch.from_numpy(np.ascontiguousarray(table).reshape(-1)).cuda()
+    out = c2_run(combo, layout, rows, peers, dsz=torch.from_numpy(d).cuda())
+    want = ref.gossip_round(X0, table, P, S, R, d=d)
+    for w in range(N):
+        assert np.array_equal(bits(out[w, :P].cpu().numpy()), bits(want[w])), (layout, w)
+
+
+@pytest.mark.parametrize("layout", ["rows", "tiled"])
+def test_c2_resnet18_full_dynamic_round_elementwise(combo, ref, layout):
+    """Sec. 4.2 on the whole c2 arena: offline workers, newcomers and active ones mixed."""
+    wl = combo.workloads.WORKLOADS["c2_resnet18"]
+    N, P, S, R = wl.N, wl.P, wl.S, wl.R
+    rows = torch.full((N, wl.ld), float("nan"), dtype=torch.float32, device="cuda")
+    combo.workloads.fill_params(rows, wl)
+    X0 = host_rows(rows, P)
+    status = np.ones(N, np.uint8)
+    status[[3, 17, 30]] = 0                          # offline
+    status[[5, 6, 22]] = 2                           # newcomers
+    table = ref.make_peer_table_dynamic(status, N, S, R, wl.hash_seed, 2)
+    st_dev = torch.from_numpy(status).cuda()
+    peers = torch.empty(N * S * R, dtype=torch.int32, device="cuda")
+    combo.make_peer_table_dynamic(peers, st_dev, N, S, R, wl.hash_seed, 2)
+    assert np.array_equal(peers.cpu().numpy().reshape(table.shape), table)
+    out = c2_run(combo, layout, rows, peers, status=st_dev)
+    want = ref.gossip_round_dynamic(X0, table, status, P, S, R)
+    for w in range(N):
+        assert np.array_equal(bits(out[w, :P].cpu().numpy()), bits(want[w])), (layout, w)
