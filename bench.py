@@ -537,7 +537,7 @@ def measure(combo, wl, args, layout, steps, warmup, trials, with_oracle, cpu_bud
     one_launch = bool(args.one_launch) and R <= 8 and (is_tiled or combo.round_kernel_kind(N, R) == 1)
     g1 = None if grads is None else grads.reshape((1,) + tuple(grads.shape))
 
-    def step(ev=None):
+    def step(ev=None, stream=stream):
         cur, rnd = state["cur"], state["round"]
         if one_launch:
             if ev is not None:
@@ -595,6 +595,29 @@ def measure(combo, wl, args, layout, steps, warmup, trials, with_oracle, cpu_bud
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         runs.append((t1 - t0, sorted(a.elapsed_time(b) for a, b in events)))
+    if args.graph:
+        # the same `steps` steps captured once into a HIP graph (the library never allocates,
+        # copies or synchronises) and replayed: what is left when launch overhead is taken away
+        try:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for k in range(steps):
+                    step(stream=torch.cuda.current_stream())
+            graph.replay()
+            torch.cuda.synchronize()
+            walls = []
+            for _ in range(trials):
+                t0 = time.perf_counter()
+                graph.replay()
+                torch.cuda.synchronize()
+                walls.append(time.perf_counter() - t0)
+            walls.sort()
+            res["graph_replay"] = {"rounds_per_s": steps / walls[len(walls) // 2],
+                                   "ms_per_step": walls[len(walls) // 2] / steps * 1e3,
+                                   "steps_per_graph": steps, "launches_per_graph": steps * (1 if one_launch else 2)}
+            del graph
+        except Exception as e:  # noqa: BLE001 - an extra: the eager figures stand on their own
+            res["graph_replay"] = {"error": str(e)[:200]}
     runs.sort(key=lambda r: r[0])
     wall, kern_ms = runs[len(runs) // 2]                 # the median trial
     res["trial_rounds_per_s"] = sorted(steps / r[0] for r in runs)
@@ -656,8 +679,10 @@ def main():
                          "for launch-bound sizes)")
     ap.add_argument("--shape", default="", help="ad-hoc workload N,P,S,R instead of a named one")
     ap.add_argument("--tiled-cols", type=int, default=0, help="tile width of the tiled layout")
+    ap.add_argument("--no-graph", dest="graph", action="store_false",
+                    help="skip the HIP-graph replay of the timed steps (graph_replay in the record)")
     ap.add_argument("--no-cpu-baseline", action="store_true",
-                    help="skip the oracle: no parity field and no cpu_baseline (profiling runs)")
+                    help="profiling runs: skip the oracle (no parity field, no cpu_baseline) and the graph replay")
     ap.add_argument("--cpu-budget", type=float, default=15.0,
                     help="seconds of CPU work for the oracle baseline (whole rounds)")
     ap.add_argument("--sweep-paper", action="store_true",
@@ -701,6 +726,8 @@ def main():
         return extras(combo, wl)
 
     oracle = not args.no_cpu_baseline
+    if args.no_cpu_baseline:
+        args.graph = False                     # profiling runs: the timed eager launches only
     head = measure(combo, wl, args, args.layout, args.steps, args.warmup, args.trials, oracle,
                    args.cpu_budget)
     torch.cuda.empty_cache()
@@ -770,6 +797,8 @@ def main():
     }
     if "parity" in head:
         out["parity"] = head["parity"]
+    if "graph_replay" in head:
+        out["graph_replay"] = head["graph_replay"]
     if per_config:
         out["per_config"] = per_config
     if "cpu_baseline" in head:

@@ -47,6 +47,9 @@ def test_bench_prints_one_json_line_with_the_required_fields():
     assert p["columns_checked"] == p["of_columns"] == 65536
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["cores"] == 1 and c["value"] > 0 and c["sample"] and c["cpu_model"]
+    # the same steps replayed from one HIP graph: launch overhead gone, so at least as fast here
+    g = d["graph_replay"]
+    assert "error" not in g and g["steps_per_graph"] == 5 and g["rounds_per_s"] > 0.8 * d["value"]
     # beside the single-thread figure of record: the same library from parallel threads
     assert c["all_cores"]["value"] > 0 and c["all_cores"]["equals_single_call_on_sampled_windows"]
 
