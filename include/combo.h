@@ -393,7 +393,9 @@ int combo_bandwidth_probe(int kind, float* d_dst, const float* d_src, int32_t N,
  *                          through its own contiguous eighth of the strips; k >= 3: the XCDs
  *                          take turns at runs of k consecutive strips; 0: automatic (runs of
  *                          16 tiles for tiled arenas, 32 from 7 GiB per matrix on, where
- *                          they measure 1-7 % faster; strip i for row-major ones)
+ *                          they measure 1-7 % faster; for row-major arenas runs that give an
+ *                          XCD 2 KiB of consecutive columns of a row per turn: 4 strips of
+ *                          128 columns, 8 of 64, strip i for wider strips)
  *   COMBO_TUNE_SLAB_THREADS slab kernel: workgroup size; 0: automatic (256 threads for slabs of up
  *                          to 12 KiB, else 512), or 256, 512
  *   COMBO_TUNE_SLAB_LDS_FLOOR slab kernel: least LDS bytes a launch asks for (1..65536); above
