@@ -402,7 +402,10 @@ int combo_bandwidth_probe(int kind, float* d_dst, const float* d_src, int32_t N,
  *                          what the kernel uses it only lowers the number of workgroups
  *                          resident per compute unit; 0: automatic (24 KiB for 256-thread
  *                          workgroups of uniform-weight static rounds with R <= 4 on arenas
- *                          below 7 GiB per matrix, where six resident workgroups beat eight)
+ *                          below 7 GiB per matrix, where six resident workgroups beat eight;
+ *                          36 KiB with one fused local step and 44 KiB with more, so that
+ *                          four or three workgroups are resident, the gradient slabs
+ *                          being in flight as well)
  *   COMBO_TUNE_TILE_COLS   row-tile kernel: columns of one worker handled by one
  *                          workgroup: 0 = automatic (2048, or 1024 for more than 384
  *                          workers), or 1024, 2048, 4096
