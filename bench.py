@@ -199,6 +199,12 @@ def extras(combo, wl):
              time_kernel(lambda: combo.bandwidth_probe(combo.PROBE_MULTI_READ, arena[1], arena[0], P, param=k,
                                                        stream=stream), stream),
              4 * (k + 1) * N * (P // 1024) * 1024, note="bytes = (k reads + 1 write) per element as issued")
+    # what the aggregation phase draws on: conflict-free 128-bit LDS reads, 8 workgroups per CU
+    lds_wgs, lds_iters = 2048, 4000
+    emit("probe: LDS reads, 128-bit, conflict-free, 2048 workgroups of 256 threads", time_kernel(
+        lambda: combo.bandwidth_probe(combo.PROBE_LDS_READ, arena[1], None, P, cols=lds_wgs, param=lds_iters,
+                                      stream=stream), stream, reps=5, warm=1),
+        lds_wgs * 256 * 8 * 16 * lds_iters, note="bytes = LDS bytes read (no HBM traffic)")
     emit("torch copy_ of one arena half", time_kernel(
         lambda: arena[1].copy_(arena[0]), stream), 8 * N * ld, note="bytes = read + write")
     emit("round with R=0, row-major (copy through the slab kernel)", time_kernel(

@@ -366,6 +366,12 @@ int combo_aggregation_divergence_noalloc(double* d_dist2, const float* d_x, int6
  *                           d_src, one workgroup per (1024 columns, row), rows in
  *                           worker-major order: param read streams and one write stream with
  *                           no reuse out of LDS
+ *   COMBO_PROBE_LDS_READ    no global memory traffic: `cols` workgroups of 256 threads each
+ *                           fill 8 KiB of LDS and read it `param` x 8 times per thread with
+ *                           conflict-free 128-bit reads (the lanes of a wavefront read 64
+ *                           consecutive words, as the aggregation phase of a round does);
+ *                           LDS bytes read = cols * 256 * 8 * 16 * param; d_dst[workgroup]
+ *                           receives a checksum (cols <= N*ld), d_src may be NULL
  * Errors: COMBO_EINVAL for an unknown kind, bad sizes or pointers, or a cols/param the
  * probe does not cover; COMBO_EALIAS for overlapping buffers.
  */
@@ -375,7 +381,8 @@ enum {
     COMBO_PROBE_WRITE = 2,
     COMBO_PROBE_ROW_CHUNKS = 3,
     COMBO_PROBE_TILES = 4,
-    COMBO_PROBE_MULTI_READ = 5
+    COMBO_PROBE_MULTI_READ = 5,
+    COMBO_PROBE_LDS_READ = 6
 };
 int combo_bandwidth_probe(int kind, float* d_dst, const float* d_src, int32_t N, int64_t ld, int64_t P,
                           int32_t cols, int32_t param, void* stream);

@@ -14,6 +14,6 @@ from .binding import (ComboError, get_tune, round_kernel_kind, lib, local_sgd_th
                       tiled_cols, tiled_elems, pack_tiled, unpack_tiled,
                       segment_gossip_round_tiled, local_sgd_steps_then_gossip_tiled,
                       aggregation_divergence_tiled, round_hashed, aggregation_divergence_noalloc, round_relayout, bandwidth_probe, PROBE_COPY, PROBE_READ, PROBE_WRITE,
-                      PROBE_ROW_CHUNKS, PROBE_TILES, PROBE_MULTI_READ,  # noqa: F401
+                      PROBE_ROW_CHUNKS, PROBE_TILES, PROBE_MULTI_READ, PROBE_LDS_READ,  # noqa: F401
                       segment_gossip_round, strerror, tune, TUNE_FUSED_MODE, TUNE_TILE_COLS,
                       TUNE_XCD_SWIZZLE, TUNE_KERNEL, TUNE_SLAB_COLS, TUNE_SLAB_ORDER, TUNE_SLAB_THREADS, TUNE_SLAB_LDS_FLOOR, LIB_PATH)

@@ -469,7 +469,7 @@ def round_relayout(dst, dst_tile_cols, src, src_tile_cols, peers, N, P, S, R, *,
     return dst
 
 
-PROBE_COPY, PROBE_READ, PROBE_WRITE, PROBE_ROW_CHUNKS, PROBE_TILES, PROBE_MULTI_READ = range(6)
+PROBE_COPY, PROBE_READ, PROBE_WRITE, PROBE_ROW_CHUNKS, PROBE_TILES, PROBE_MULTI_READ, PROBE_LDS_READ = range(7)
 
 
 def bandwidth_probe(kind, dst, src, P, cols=0, param=None, stream=None):

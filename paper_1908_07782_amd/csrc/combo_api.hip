@@ -596,9 +596,9 @@ int combo_aggregation_divergence_noalloc(double* d_dist2, const float* d_x, int6
 
 int combo_bandwidth_probe(int kind, float* d_dst, const float* d_src, int32_t N, int64_t ld, int64_t P,
                           int32_t cols, int32_t param, void* stream) {
-    if (kind < COMBO_PROBE_COPY || kind > COMBO_PROBE_MULTI_READ) return COMBO_EINVAL;
+    if (kind < COMBO_PROBE_COPY || kind > COMBO_PROBE_LDS_READ) return COMBO_EINVAL;
     if (N < 1 || P < 1 || ld < P || d_dst == nullptr) return COMBO_EINVAL;
-    if (kind != COMBO_PROBE_WRITE && d_src == nullptr) return COMBO_EINVAL;
+    if (kind != COMBO_PROBE_WRITE && kind != COMBO_PROBE_LDS_READ && d_src == nullptr) return COMBO_EINVAL;
     if (!aligned16(d_dst) || !aligned16(d_src) || ld % 4 != 0) return COMBO_EINVAL;
     if ((uint64_t)ld > (UINT64_MAX / 4) / (uint64_t)N) return COMBO_ERANGE;
     const uint64_t bytes = (uint64_t)N * (uint64_t)ld * 4;

@@ -150,6 +150,42 @@ __global__ __launch_bounds__(kProbeThreads) void probe_multi_read_kernel(float* 
     store4_stream(dst + (size_t)w * (size_t)ld + col, acc);
 }
 
+// LDS read rate: every workgroup fills an 8 KiB block of LDS with its word indices and reads
+// it `iters` x 8 times per thread with conflict-free 128-bit reads (the lanes of a wavefront read
+// 64 consecutive words, as the aggregation phase of the slab kernel does), adding what it reads;
+// the workgroup's sum goes to dst[workgroup].  No global memory traffic to speak of.
+constexpr int kLdsProbeWords = 512;
+__global__ __launch_bounds__(kProbeThreads) void probe_lds_read_kernel(float* __restrict__ dst, int iters) {
+    __shared__ v4f block[kLdsProbeWords];
+    __shared__ float part[kProbeThreads];
+    for (int i = threadIdx.x; i < kLdsProbeWords; i += kProbeThreads)
+        block[i] = v4f{(float)i, 0.0f, 0.0f, 1.0f};
+    __syncthreads();
+    v4f acc = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+    int idx = (int)threadIdx.x;
+    for (int it = 0; it < iters; ++it) {
+        // the index is made opaque to the compiler in every iteration, so that no read is carried
+        // over from the iteration before (the eight words of a thread recur)
+        asm volatile("" : "+v"(idx));
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const v4f v = block[(idx + u * 64) & (kLdsProbeWords - 1)];
+            acc.x += v.x;
+            acc.y += v.y;
+            acc.z += v.z;
+            acc.w += v.w;
+        }
+        idx = (idx + 64) & (kLdsProbeWords - 1);
+    }
+    part[threadIdx.x] = acc.x + acc.w;
+    __syncthreads();
+    for (int half = kProbeThreads / 2; half >= 1; half >>= 1) {
+        if ((int)threadIdx.x < half) part[threadIdx.x] += part[threadIdx.x + half];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) dst[blockIdx.x] = part[0];
+}
+
 }  // namespace
 
 // kind: 0 linear copy, 1 read only, 2 write only (n = N*ld floats, `param` = 128-bit words in
@@ -157,8 +193,9 @@ __global__ __launch_bounds__(kProbeThreads) void probe_multi_read_kernel(float* 
 // stores written through to device scope; cols >> 4: blocks per XCD turn);
 // 3 row-chunk copy, 4 tile copy (`cols` columns per strip; `param` > 1: the XCDs take turns at
 // runs of `param` consecutive strips);
-// 5 multi-read pass (`param` = rows read per output).  Only whole 128-bit words, strips and
-// tiles are touched.  Returns hipErrorInvalidValue for shapes the probes do not cover.
+// 5 multi-read pass (`param` = rows read per output); 6 LDS read rate (`cols` workgroups, each
+// reading 8 KiB of LDS `param` x 8 times per thread; dst[workgroup] receives a checksum).  Only
+// whole 128-bit words, strips and tiles are touched.  Returns hipErrorInvalidValue for shapes the probes do not cover.
 hipError_t launch_bandwidth_probe(int kind, float* dst, const float* src, int32_t N, int64_t ld, int64_t P,
                                   int cols, int param, hipStream_t st) {
     const uint64_t n4 = (uint64_t)N * (uint64_t)ld / 4;
@@ -212,6 +249,11 @@ hipError_t launch_bandwidth_probe(int kind, float* dst, const float* src, int32_
             return hipErrorInvalidValue;
         hipLaunchKernelGGL(probe_multi_read_kernel, dim3((uint32_t)(tiles * (uint64_t)N)), dim3(kProbeThreads), 0,
                            st, dst, src, ld, N, param, (uint32_t)tiles);
+        return hipGetLastError();
+    }
+    if (kind == 6) {
+        if (cols < 1 || (uint64_t)cols > n4 * 4 || param < 1 || param > (1 << 20)) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(probe_lds_read_kernel, dim3((uint32_t)cols), dim3(kProbeThreads), 0, st, dst, param);
         return hipGetLastError();
     }
     return hipErrorInvalidValue;

@@ -125,7 +125,7 @@ def test_bandwidth_probe_argument_errors(L):
     f.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64,
                   ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
     assert f(-1, FAKE_A, FAKE_B, 4, 1024, 1000, 0, 1, None) == EINVAL        # unknown kind
-    assert f(6, FAKE_A, FAKE_B, 4, 1024, 1000, 0, 1, None) == EINVAL
+    assert f(7, FAKE_A, FAKE_B, 4, 1024, 1000, 0, 1, None) == EINVAL
     assert f(0, None, FAKE_B, 4, 1024, 1000, 0, 1, None) == EINVAL
     assert f(0, FAKE_A, None, 4, 1024, 1000, 0, 1, None) == EINVAL           # only the write probe needs no source
     assert f(0, FAKE_A, FAKE_B, 4, 999, 1000, 0, 1, None) == EINVAL          # ld < P

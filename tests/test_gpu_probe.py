@@ -96,3 +96,21 @@ def test_multi_read_pass_adds_k_rows_in_order(combo, N, P, ld, k):
         want = want + np.roll(src_h, -j, axis=0)[:, :covered]       # fp32 adds, in row order
     assert np.array_equal(bits(got[:, :covered]), bits(want))
     assert np.isnan(got[:, covered:]).all()
+
+
+def test_lds_read_probe_reads_what_it_says(combo):
+    """Every thread of a workgroup reads iters x 8 words of the 8 KiB block, 64 lanes on 64
+    consecutive words; the checksum is the sum of the word indices read plus the number of reads."""
+    iters, wgs = 4, 37
+    dst = torch.full((4, 1024), float("nan"), dtype=torch.float32, device="cuda")
+    combo.bandwidth_probe(combo.PROBE_LDS_READ, dst, None, 1000, cols=wgs, param=iters)
+    got = dst.cpu().numpy().reshape(-1)
+    want = 0
+    for t in range(256):
+        idx = t
+        for it in range(iters):
+            for u in range(8):
+                want += ((idx + u * 64) & 511) + 1
+            idx = (idx + 64) & 511
+    assert np.array_equal(got[:wgs], np.full(wgs, float(want), np.float32))
+    assert np.isnan(got[wgs:]).all()
