@@ -65,16 +65,24 @@ def time_kernel(fn, stream, reps=20, warm=3):
 
 def sweep_paper(combo, P, layout="rows"):
     """The paper's own sweeps as bandwidth curves (Sec. 5.2: 30 workers; R = 1..16 at
-    S = 10; S = 1..10 at R = 2).  One JSON line per point."""
+    S = 10; S = 1..10 at R = 2; and 20, 30, 40 workers at the default S = 10, R = 2).  One
+    JSON line per point."""
     import torch
-    N = 30
+    sweep_paper_workers(combo, 30, P, layout,
+                        [("R", 10, r) for r in (1, 2, 3, 4, 6, 8, 12, 16, 29)] +
+                        [("S", s, 2) for s in (1, 2, 3, 4, 6, 8, 10)] + [("N", 10, 2)])
+    for N in (20, 40):
+        torch.cuda.empty_cache()
+        sweep_paper_workers(combo, N, P, layout, [("N", 10, 2)])
+
+
+def sweep_paper_workers(combo, N, P, layout, points):
+    import torch
     ld = combo.workloads.row_pitch(P)
     wl = combo.workloads.small_case(N, P, 10, 2, scale=0.02)
     rows = torch.zeros((N, ld), dtype=torch.float32, device="cuda")
     combo.workloads.fill_params(rows, wl)
     stream = torch.cuda.current_stream()
-    points = [("R", 10, r) for r in (1, 2, 3, 4, 6, 8, 12, 16, 29)] + \
-             [("S", s, 2) for s in (1, 2, 3, 4, 6, 8, 10)]
     ws = torch.empty(combo.aggregation_divergence_workspace(N, P) // 8, dtype=torch.float64, device="cuda")
     d2 = torch.empty(N, dtype=torch.float64, device="cuda")
     tiled = layout == "tiled"
