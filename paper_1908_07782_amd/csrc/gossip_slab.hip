@@ -31,7 +31,9 @@ int slab_threads(int32_t N, int W) {
 // does not hold where a workgroup spends longer between its loads and its stores: with
 // dataset-size weights or dynamic workers the two extra workgroups are worth 8-10 % (c2
 // weighted: 0.49 vs 0.55 ms), from R = 8 on 2-5 %, and on the largest arena 1 %.  512-thread
-// workgroups are four per compute unit anyway.
+// workgroups are four per compute unit anyway.  Slabs between 10 and 12 KiB (worker counts
+// between powers of two) do best with five (32 KiB each): 24 workers 6.33 against 6.07 TB/s,
+// 48 workers 6.18 against 5.87; about 50-60 KiB of slabs per compute unit in every case.
 // With fused local steps a workgroup has the gradient slab in flight as well (and with more than
 // one step the next slice on top), and what the memory system takes best is 64-80 KiB of loads
 // per compute unit, as for every streaming kernel here: four resident workgroups (36 KiB each)
@@ -47,9 +49,10 @@ size_t slab_lds_request(const RoundArgs& a, int W, bool hashed) {
     size_t floor_bytes = (size_t)g_slab_lds_floor.load();
     const bool short_aggregation = a.R <= 4 && a.dsz == nullptr && a.status == nullptr;
     const bool small_arena = (uint64_t)a.N * (uint64_t)a.P * sizeof(float) < (7ull << 30);
+    const size_t slab_bytes = (size_t)a.N * (size_t)W * sizeof(float);
     if (floor_bytes == 0 && slab_threads(a.N, W) == 256 && short_aggregation) {
         if (a.grad != nullptr) floor_bytes = (a.tau >= 2 ? 44 : 36) * 1024;
-        else if (small_arena) floor_bytes = 24 * 1024;
+        else if (small_arena) floor_bytes = slab_bytes > 10 * 1024 ? 32 * 1024 : 24 * 1024;
     }
     return used > floor_bytes ? used : floor_bytes;
 }
