@@ -130,3 +130,24 @@ def test_divergence_errors(combo):
     small = torch.zeros(1, dtype=torch.float64, device="cuda")
     with pytest.raises(combo.ComboError):
         combo.aggregation_divergence(out, x[:4], 1000, small)
+
+
+@pytest.mark.parametrize("N,weighted", [(1, True), (3, False), (5, True), (30, False), (100, True)])
+def test_identical_rows_have_no_divergence_up_to_the_rounding_of_the_mean(combo, ref, N, weighted):
+    """All workers hold one model (Sec. 4.1 initialisation): Definition 2 gives zero.  The kernel
+    forms the mean as a sum times a rounded reciprocal, so its mean is off by at most
+    (N+3) * 2^-53 relative and dist^2 by at most the square of that times |mean|^2: far below
+    anything a model distance can resolve, but not exactly zero unless N is a power of two."""
+    P = 100_003
+    rng = np.random.default_rng(N)
+    row = rng.normal(0, 0.02, P).astype(np.float32)
+    Xh = np.tile(row, (N, 1))
+    ld = combo.workloads.row_pitch(P)
+    x = torch.full((N, ld), float("nan"), dtype=torch.float32, device="cuda")
+    x[:, :P] = torch.from_numpy(Xh).cuda()
+    d = combo.workloads.dataset_sizes(N, 5, "cuda") if weighted else None
+    got = gpu_divergence(combo, x, P, d)
+    want = ref.aggregation_divergence(Xh, d=None if d is None else d.cpu().numpy())
+    assert np.all(want == 0.0)
+    bound = ((N + 3) * 2.0 ** -53) ** 2 * float(np.sum(row.astype(np.float64) ** 2))
+    assert np.all(got >= 0.0) and np.all(got <= bound), (got, bound)
